@@ -1,0 +1,250 @@
+/*
+ * tasc.h -- C ABI of the MI355X (gfx950) library for TASC-spec: batched, greedy, n-gram-drafted
+ * speculative decoding of a small decoder-only language model.
+ *
+ * The method is the inference-time method of "Task-Centric Acceleration of Small-Language Models"
+ * (section "n-Gram Speculative Decoding Method"): a drafter made of pruned corpus n-gram tables M_n
+ * (n <= n_max), queried in descending order of n with the most frequent token as the fallback,
+ * mixed with an n-gram drafter over the available context,
+ *     p_mixed(x|c) = lambda p_corp(x|c) + (1 - lambda) p_prompt(x|c),
+ * proposes a run of tokens that the target model verifies in a single forward pass, of which a
+ * prefix is accepted (subsection "Speculative Decoding"; greedy, beam size 1, p_min = 5 and
+ * lambda = 0.75 in the paper's Results).
+ *
+ * Conventions
+ *   - Every function returns a tasc_status; on error nothing is written to the outputs and
+ *     tasc_last_error() holds a thread-local message.
+ *   - "device" pointers are HIP device memory of the current device, "host" pointers ordinary
+ *     host memory.  The caller owns every buffer it passes in; the library owns only the opaque
+ *     handles (and the device memory it allocates for the n-gram tables and the packed weights)
+ *     and releases them in *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Unless stated
+ *     otherwise a call only enqueues work on `stream`; results are valid once the stream has
+ *     been synchronised.
+ *   - Same inputs give bit-identical outputs, run to run.
+ *   - There is no CPU fallback: without a gfx950 device every compute call fails with TASC_EHIP.
+ */
+#ifndef TASC_H
+#define TASC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tasc_status;
+enum {
+    TASC_OK = 0,
+    TASC_EINVAL = -1,  /* null pointer, shape or range error                       */
+    TASC_ENOMEM = -2,  /* caller buffer too small, allocation failure, table full  */
+    TASC_EHIP = -3,    /* HIP runtime error (text in tasc_last_error)              */
+    TASC_ESTATE = -4   /* call out of order (e.g. verify before prefill)           */
+};
+
+typedef enum { TASC_MEM_HOST = 0, TASC_MEM_DEVICE = 1 } tasc_mem;
+typedef enum { TASC_F32 = 0, TASC_BF16 = 1 } tasc_dtype;
+
+#define TASC_MAX_ORDER 8   /* n_max <= 8 and n_max * ceil(log2(vocab)) <= 128 */
+#define TASC_MAX_K 15      /* at most 15 draft tokens per step                */
+
+typedef struct tasc_model tasc_model;     /* packed weights, LM-head bias, RoPE table            */
+typedef struct tasc_ngram tasc_ngram;     /* corpus tables M_2..M_nmax and the fallback token    */
+typedef struct tasc_session tasc_session; /* B sequences: committed tokens, lengths, paged KV    */
+
+const char* tasc_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Corpus n-gram drafter (section "Proposed Method: TASC-spec", first paragraph).
+ * ---------------------------------------------------------------------------------------- */
+
+/*
+ * Builds M_n for n = 2..n_max from the n-gram frequencies of the corpus, prunes every element
+ * whose count is below p_min, and finds the most frequent token.
+ *   tokens       int32[doc_offsets[n_docs]], every token in [0, vocab); host or device per `where`
+ *   doc_offsets  HOST int64[n_docs + 1], non-decreasing, doc_offsets[0] = 0; n-grams never span
+ *                two documents.  The corpus must hold fewer than 2^32 - 1 tokens.
+ *   n_max        in [2, TASC_MAX_ORDER];  p_min >= 1.
+ * An element (c, x) of M_n is kept iff count(c, x) >= p_min; per kept context c the table holds
+ * T(c) = sum of kept counts and its most frequent kept successor (smallest id among equals).
+ * Synchronous: allocates device memory, runs on `stream` and waits for it.  *out is owned by the
+ * library until tasc_ngram_destroy.
+ */
+tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* doc_offsets, int64_t n_docs,
+                             int32_t vocab, int32_t n_max, int32_t p_min, tasc_mem where,
+                             void* stream, tasc_ngram** out);
+void tasc_ngram_destroy(tasc_ngram* ng);
+
+/*
+ * Canonical dump of M_order for parity checks: the kept n-grams sorted by their tokens.
+ *   ctx_next  HOST int32[cap, order] (context tokens then the successor), counts HOST uint32[cap].
+ *   n_inout   in: cap (rows available); out: number of kept n-grams.  With NULL arrays only the
+ *             count is returned.  TASC_ENOMEM if cap is too small (count still returned).
+ */
+tasc_status tasc_ngram_export(const tasc_ngram* ng, int32_t order, int32_t* ctx_next,
+                              uint32_t* counts, int64_t* n_inout);
+/* Same for the per-context aggregates: ctx HOST int32[cap, order-1], total/top/top_count HOST [cap]. */
+tasc_status tasc_ngram_export_contexts(const tasc_ngram* ng, int32_t order, int32_t* ctx,
+                                       uint32_t* total, int32_t* top, uint32_t* top_count,
+                                       int64_t* n_inout);
+/* Most frequent corpus token (smallest id among equals) and, if non-NULL, HOST uint32[vocab] counts. */
+tasc_status tasc_ngram_unigram(const tasc_ngram* ng, int32_t* fallback, uint32_t* counts);
+
+typedef struct {
+    int64_t n_tokens;
+    int64_t windows[TASC_MAX_ORDER + 1];   /* windows counted per order                 */
+    int64_t distinct[TASC_MAX_ORDER + 1];  /* distinct n-grams before pruning           */
+    int64_t kept[TASC_MAX_ORDER + 1];      /* n-grams kept after pruning                */
+    int64_t contexts[TASC_MAX_ORDER + 1];  /* kept contexts                             */
+    double build_ms;                       /* device time of the whole build            */
+    double count_ms;                       /* device time of the counting kernels alone */
+} tasc_ngram_stats;
+tasc_status tasc_ngram_get_stats(const tasc_ngram* ng, tasc_ngram_stats* out);
+
+/* ------------------------------------------------------------------------------------------
+ * Target model.  The paper uses the target as a black box; the architecture (pre-norm RMSNorm,
+ * RoPE with rotate-half pairing, grouped-query attention, SwiGLU, untied LM head, sparse additive
+ * bigram bias on the logits) is that of the benchmark configurations.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t dtype;      /* tasc_dtype of the matrices and of the KV cache                  */
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t max_pos;    /* RoPE table length: largest position + 1                         */
+    float rope_theta;   /* angle of pair i at position p: p * theta^(-2i/head_dim)         */
+    float rms_eps;      /* RMSNorm: x * g / sqrt(mean(x^2) + eps)                          */
+} tasc_model_desc;
+
+/*
+ * All matrices are [out_features, in_features] row-major in `dtype` (bf16 as raw 16-bit
+ * patterns); gains are fp32.  Per-layer entries are HOST arrays of n_layers pointers.  The
+ * pointed-to data may be host or device memory (`where`); it is copied, the caller may free it
+ * after the call.
+ *   embed, lm_head [vocab, d_model];  wq [n_heads*head_dim, d_model];  wk, wv [n_kv_heads*head_dim,
+ *   d_model];  wo [d_model, n_heads*head_dim];  wg, wu [d_ffn, d_model];  wd [d_model, d_ffn];
+ *   g1, g2, gf fp32 [d_model].
+ * LM-head bias (all four NULL for none): logits[v] = h . lm_head[v] + bias(u, v), u = the input
+ * token of the row; bias(u, v) = bias_val[j] if v = bias_col[j] for some j in
+ * [bias_rowptr[u], bias_rowptr[u+1]) (columns ascending within a row), else bias_base[u].
+ */
+typedef struct {
+    tasc_mem where;
+    const void* embed;
+    const void* lm_head;
+    const float* gf;
+    const void* const* wq;
+    const void* const* wk;
+    const void* const* wv;
+    const void* const* wo;
+    const void* const* wg;
+    const void* const* wu;
+    const void* const* wd;
+    const float* const* g1;
+    const float* const* g2;
+    const int64_t* bias_rowptr; /* [vocab + 1] */
+    const int32_t* bias_col;    /* [nnz]       */
+    const float* bias_val;      /* [nnz]       */
+    const float* bias_base;     /* [vocab]     */
+} tasc_weight_ptrs;
+
+/* Synchronous (copies and repacks the weights into library-owned device memory). */
+tasc_status tasc_model_create(const tasc_model_desc* desc, const tasc_weight_ptrs* w, tasc_model** out);
+void tasc_model_destroy(tasc_model* m);
+
+/* ------------------------------------------------------------------------------------------
+ * Session: `batch` sequences decoded in lock-step.
+ *   max_len   most tokens (prompt + generated + drafts in flight) a sequence may hold
+ *   max_rows  most rows per sequence in one forward: >= k + 1, also the prefill chunk length
+ * KV cache: pages of 16 positions, [page][K|V][kv_head][...], one pool per layer, all inside the
+ * caller's kv_pool; a block table maps (sequence, position / 16) to a page.  Positions whose
+ * drafts were rejected stay allocated and are overwritten by the next step ("rollback" only
+ * shortens the sequence's cached length).
+ * ---------------------------------------------------------------------------------------- */
+size_t tasc_session_kv_bytes(const tasc_model* m, int32_t batch, int32_t max_len);
+size_t tasc_session_workspace_bytes(const tasc_model* m, int32_t batch, int32_t max_len, int32_t max_rows);
+/* kv_pool and workspace: DEVICE memory, 256-byte aligned, at least the sizes above; owned by the
+ * caller and must outlive the session.  Synchronous (initialises the block table). */
+tasc_status tasc_session_create(const tasc_model* m, int32_t batch, int32_t max_len, int32_t max_rows,
+                                void* kv_pool, size_t kv_bytes, void* workspace, size_t ws_bytes,
+                                tasc_session** out);
+void tasc_session_destroy(tasc_session* s);
+
+/*
+ * Resets the session and runs the prompt forward: fills the KV cache for all prompt positions and
+ * commits, as generated token #1, the argmax at the last prompt position (the "pending" token,
+ * whose own KV is not cached yet).
+ *   prompts         int32, concatenated, host or device per `where`
+ *   prompt_offsets  HOST int64[batch + 1]; every prompt has 1..max_len tokens
+ *   max_new         tokens to generate per sequence (>= 1); a sequence that has them is frozen
+ */
+tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s, const int32_t* prompts,
+                                 const int64_t* prompt_offsets, tasc_mem where, int32_t max_new,
+                                 void* stream);
+
+typedef struct {
+    int32_t k;                       /* draft tokens per step, 0..TASC_MAX_K (0 = plain greedy)   */
+    int32_t lambda_q16;              /* round(lambda * 65536) in [0, 65536]; 49152 = 0.75         */
+    int32_t p_min_ctx;               /* pruning threshold of the context drafter (>= 1)           */
+    int32_t ctx_includes_generated;  /* 1: context = prompt + committed output; 0: prompt only    */
+} tasc_spec_params;
+
+/*
+ * Proposes k tokens for every sequence (section "Proposed Method: TASC-spec"): k times in a row,
+ * each source (corpus tables; n-gram counts of the sequence's own committed tokens) backs off from
+ * order n_max to 2 to its first matching context, the proposal is
+ *     argmax_x  q C_corp(x) T_ctx + (65536 - q) C_ctx(x) T_corp        (q = lambda_q16)
+ * i.e. the argmax of p_mixed, ties to the smallest token id; with one source matching, that
+ * source's most frequent successor; with none, the corpus' most frequent token.  A source whose
+ * weight is 0 is not consulted.  Each proposal is appended to the running context of the next.
+ *   drafts  DEVICE int32[batch, k]
+ */
+tasc_status tasc_draft(const tasc_ngram* ng, tasc_session* s, const tasc_spec_params* p,
+                       int32_t* drafts, void* stream);
+
+/*
+ * One target forward over the rows [pending, d_1..d_k] of every sequence (subsection "Speculative
+ * Decoding": the drafted tokens are verified in parallel via a single forward pass), then greedy
+ * acceptance: a_i = argmax of row i (lowest index among equals), m = the longest prefix with
+ * d_i = a_{i-1}; the sequence commits d_1..d_m and the bonus token a_m, its cached length grows by
+ * 1 + m, the new pending token is a_m.
+ *   drafts      DEVICE int32[batch, k] (ignored if k = 0)
+ *   accept_len  DEVICE int32[batch], nullable
+ *   emitted     DEVICE int32[batch, k + 1], nullable: d_1..d_m, a_m, then -1 padding
+ *   logits_dbg  DEVICE fp32[batch, k + 1, vocab], nullable: the full logits of every row
+ * A sequence that already has its max_new tokens is frozen (accept_len 0, emitted all -1).
+ */
+tasc_status tasc_verify_step(const tasc_model* m, tasc_session* s, const int32_t* drafts, int32_t k,
+                             int32_t* accept_len, int32_t* emitted, float* logits_dbg, void* stream);
+
+typedef struct {
+    int64_t steps;                       /* verify steps executed                                  */
+    int64_t emitted;                     /* tokens delivered (batch * max_new)                     */
+    int64_t accepted;                    /* draft tokens accepted over all steps and sequences     */
+    int64_t proposed;                    /* draft tokens proposed to live sequences                */
+    int64_t accept_hist[TASC_MAX_K + 1]; /* number of (step, sequence) pairs per accept length     */
+    double prefill_ms, decode_ms;        /* device time (HIP events on `stream`)                   */
+} tasc_gen_stats;
+
+/*
+ * Prefill, then draft + verify until every sequence has max_new tokens (plain greedy if p->k = 0,
+ * `ng` may then be NULL).  Synchronous.
+ *   out_tokens  DEVICE int32[batch, max_new]
+ *   trace       DEVICE int32, nullable, capacity trace_steps steps of
+ *               [batch][1 + k + (k+1) + 1] = (committed length before the step, drafts, argmax
+ *               ids, accept length) for step-by-step replay against a reference
+ *   stats       HOST, nullable
+ */
+tasc_status tasc_generate(const tasc_model* m, const tasc_ngram* ng, tasc_session* s,
+                          const int32_t* prompts, const int64_t* prompt_offsets, tasc_mem where,
+                          int32_t max_new, const tasc_spec_params* p, int32_t* out_tokens,
+                          int32_t* trace, int32_t trace_steps, tasc_gen_stats* stats, void* stream);
+
+/* Copies sequence b's committed tokens (prompt + generated) to HOST int32[cap]; *n = how many.
+ * Synchronises `stream`. */
+tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* tokens, int32_t cap,
+                                    int32_t* n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TASC_H */

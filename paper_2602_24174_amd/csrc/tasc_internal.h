@@ -1,0 +1,178 @@
+// Internal definitions shared by the translation units of libtasc (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include <vector>
+#include "../../include/tasc.h"
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+void tasc_set_error(const char* fmt, ...);
+
+#define TASC_HIP(expr)                                                                    \
+    do {                                                                                  \
+        hipError_t _e = (expr);                                                           \
+        if (_e != hipSuccess) {                                                           \
+            tasc_set_error("%s:%d: %s -> %s", __FILE__, __LINE__, #expr, hipGetErrorString(_e)); \
+            return TASC_EHIP;                                                             \
+        }                                                                                 \
+    } while (0)
+
+#define TASC_REQUIRE(cond, ...)            \
+    do {                                   \
+        if (!(cond)) {                     \
+            tasc_set_error(__VA_ARGS__);   \
+            return TASC_EINVAL;            \
+        }                                  \
+    } while (0)
+
+#define TASC_LAUNCH_CHECK()                                                          \
+    do {                                                                             \
+        hipError_t _e = hipGetLastError();                                           \
+        if (_e != hipSuccess) {                                                      \
+            tasc_set_error("%s:%d: launch -> %s", __FILE__, __LINE__, hipGetErrorString(_e)); \
+            return TASC_EHIP;                                                        \
+        }                                                                            \
+    } while (0)
+
+// ---------------------------------------------------------------- n-gram tables
+// One 32-byte slot of a finished (read-only) table.  The key is the packed token string
+// (token j at bit j*bits of the 128-bit integer hi:lo).  Context tables: a = T (sum of kept
+// successor counts), b = most frequent kept successor, c = its count.  Full tables: a = count.
+// a == 0 marks an empty slot.
+struct __attribute__((aligned(32))) TascSlot {
+    u64 lo, hi;
+    u32 a, b, c, d;
+};
+
+struct TascOrderTab {
+    const TascSlot* ctx;
+    const TascSlot* full;
+    u64 ctx_mask;   // capacity - 1 (capacity is a power of two); 0 and ctx == nullptr if the order is empty
+    u64 full_mask;
+};
+
+struct TascNgramView {
+    TascOrderTab ord[TASC_MAX_ORDER + 1];   // indexed by n
+    int32_t n_max, bits, fallback, vocab;
+};
+
+struct tasc_ngram {
+    TascNgramView view;
+    TascSlot* slots[TASC_MAX_ORDER + 1][2];
+    u32* unigram;   // device [vocab]
+    int32_t p_min;
+    tasc_ngram_stats stats;
+};
+
+__host__ __device__ inline u64 tasc_mix64(u64 x) {
+    x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27; x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+__host__ __device__ inline u64 tasc_hash_key(u64 lo, u64 hi, int ntok) {
+    return tasc_mix64(lo ^ tasc_mix64(hi + 0x9E3779B97F4A7C15ull * (u64)(ntok + 1)));
+}
+// appends token t as element j of a packed key
+__host__ __device__ inline void tasc_key_put(u64& lo, u64& hi, int j, int bits, u32 t) {
+    int sh = j * bits;
+    if (sh < 64) {
+        lo |= (u64)t << sh;
+        if (sh + bits > 64) hi |= (u64)t >> (64 - sh);
+    } else {
+        hi |= (u64)t << (sh - 64);
+    }
+}
+__host__ __device__ inline u32 tasc_key_get(u64 lo, u64 hi, int j, int bits) {
+    int sh = j * bits;
+    u64 v;
+    if (sh < 64) {
+        v = lo >> sh;
+        if (sh + bits > 64) v |= hi << (64 - sh);
+    } else {
+        v = hi >> (sh - 64);
+    }
+    return (u32)(v & ((1ull << bits) - 1));
+}
+
+// ---------------------------------------------------------------- model
+struct TascLayerW {
+    const void* wqkv;  // [(H + 2 Hkv) hd, d]: q heads, k heads, v heads
+    const void* wo;    // [d, H hd]
+    const void* wgu;   // [2F, d]: blocks of 16 gate rows followed by the 16 up rows of the same features
+    const void* wd;    // [d, F]
+    const float* g1;
+    const float* g2;
+};
+
+struct tasc_model {
+    tasc_model_desc desc;
+    std::vector<TascLayerW> layers;
+    void* embed;
+    void* lm_head;
+    float* gf;
+    float* rope_cos;   // [max_pos, hd/2]
+    float* rope_sin;
+    int64_t* bias_rowptr;
+    int32_t* bias_col;
+    float* bias_val;
+    float* bias_base;
+    std::vector<void*> allocs;
+};
+
+// ---------------------------------------------------------------- session
+#define TASC_KV_BLOCK 16
+#define TASC_DRAFT_MAX_LEN 4096   // longest sequence the draft kernel can hold in LDS
+#define TASC_LM_STRIP 128         // vocabulary columns per partial-argmax strip
+
+struct TascSessDev {
+    // per-sequence state (device)
+    int32_t* tokens;     // [B, max_len] committed tokens: prompt then generated (last one = pending)
+    int32_t* n_tok;      // [B] committed tokens
+    int32_t* n_prompt;   // [B]
+    int32_t* cached;     // [B] positions whose K,V are valid in the cache
+    int32_t* n_emit;     // [B] generated tokens so far
+    int32_t* block_tab;  // [B, max_blocks]
+    // per-forward row metadata
+    int32_t* row_tok;    // [M_max] input token of every row (clamped into the vocabulary)
+    int32_t* n_rows;     // [B] active rows of the sequence in this forward
+    int32_t* pos0;       // [B] position of the sequence's first row
+    int32_t* sel_rows;   // [M_max] rows fed to the LM head (negative: none, row 0 is used and ignored)
+    int32_t* sel_tok;    // [M_max] input token of every LM-head row (its bias row)
+    // counters: [0] sequences that reached max_new, [1] min n_emit scratch, [2] steps, [3] accepted,
+    // [4] proposed, [8..8+TASC_MAX_K] accept-length histogram
+    u64* counters;
+    // activations
+    float* x;            // [M_max, d] residual stream
+    void* h;             // [M_max, d]   normalised activations, model dtype
+    float* qkv;          // [M_max, (H + 2Hkv) hd]
+    void* q;             // [M_max, H hd] rotated queries, model dtype
+    void* att;           // [M_max, H hd]
+    void* act;           // [M_max, F]
+    float* part_val;     // [M_max, n_strips]
+    int32_t* part_idx;   // [M_max, n_strips]
+    int32_t* amax;       // [M_max] argmax token of every LM-head row
+    float* att_part;     // attention split partials
+    int32_t* drafts;     // [B, TASC_MAX_K] used by tasc_generate
+};
+
+struct tasc_session {
+    const tasc_model* model;
+    int32_t batch, max_len, max_rows, max_blocks, n_strips;
+    int32_t max_new;
+    int32_t prefilled;
+    void* kv_pool;
+    size_t kv_layer_stride;   // elements per layer
+    size_t page_elems;        // elements per page (K and V)
+    TascSessDev d;
+    u64* host_counters;       // pinned
+};
+
+// forward.hip
+tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel,
+                              float* logits_dbg, hipStream_t st);

@@ -1,0 +1,177 @@
+"""GPU forward, verify step and generation loop against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workload as W
+from oracle import model as OM
+from oracle import ngram as ON
+
+pytestmark = pytest.mark.gpu
+
+
+def _replay(cfg, ref_tables, prompt, trace_b, k, lam, p_min_ctx, out_tokens):
+    """Oracle recomputes every step's drafts from the GPU's committed tokens and every accept length
+    from the GPU's argmax ids (no oracle transformer needed)."""
+    from gpu_util import split_trace
+    n_before, drafts, amax, acc = split_trace(trace_b, k)
+    seq = list(prompt) + [int(out_tokens[0])]
+    for s in range(trace_b.shape[0]):
+        if acc[s] < 0:
+            continue                                       # frozen: already has its tokens
+        assert n_before[s] == len(seq)
+        if k:
+            assert drafts[s].tolist() == ON.draft(ref_tables, seq, k, lam, p_min_ctx), f"step {s}"
+        m = OM.accept_length(drafts[s].tolist(), amax[s].tolist())
+        assert m == acc[s], f"step {s}"
+        seq += drafts[s][:m].tolist() + [int(amax[s][m])]
+    gen = seq[len(prompt):]
+    assert gen[:len(out_tokens)] == out_tokens.tolist()
+
+
+def test_cfg1_end_to_end():
+    """Config 1 in full: every draft, argmax, accept length and token equals the oracle's; logits <= 1e-3."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig, split_trace
+    cfg = W.get_config("cfg1")
+    rig = Rig(cfg)
+    ref_tables = ON.build_tables_flat(rig.corpus[0], rig.corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
+    om = OM.OracleModel(cfg, rig.weights)
+    otrace = []
+    want, o_steps = OM.generate(om, rig.prompts, cfg.gen_len, cfg.k,
+                                lambda c: ON.draft(ref_tables, c, cfg.k, cfg.lambda_q16, cfg.p_min_ctx), trace=otrace,
+                                prefill_chunk=rig.max_rows)
+    out, st, tr = rig.generate(trace_steps=cfg.gen_len)
+    print(f"steps {st.steps} (oracle {o_steps}), accepted {st.accepted}/{st.proposed}, decode {st.decode_ms:.2f} ms", flush=True)
+    assert out[0].tolist() == want
+    assert st.steps == o_steps
+    n_before, drafts, amax, acc = split_trace(tr[:, 0], cfg.k)
+    for s, o in enumerate(otrace):
+        assert n_before[s] == len(o["committed"])
+        assert drafts[s].tolist() == o["drafts"]
+        assert amax[s].tolist() == o["argmax"].tolist()
+        assert acc[s] == o["accept"]
+    assert st.accepted == sum(o["accept"] for o in otrace)
+    assert sum(st.accept_hist) == st.steps
+    _replay(cfg, ref_tables, rig.prompts.tolist(), tr[:, 0], cfg.k, cfg.lambda_q16, cfg.p_min_ctx, out[0])
+    # plain greedy on the GPU gives the same tokens
+    g_out, g_st, _ = rig.generate(k=0)
+    assert g_out[0].tolist() == want and g_st.steps == cfg.gen_len - 1
+
+    # logits of single verify steps against the oracle, step by step
+    T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+    cache = om.new_cache(rig.max_len)
+    om.forward(rig.prompts.tolist(), cache)
+    cache.length = len(rig.prompts)
+    logits = torch.zeros((1, cfg.k + 1, cfg.vocab), dtype=torch.float32, device="cuda")
+    acc_d = torch.zeros(1, dtype=torch.int32, device="cuda")
+    emit_d = torch.zeros((1, cfg.k + 1), dtype=torch.int32, device="cuda")
+    worst = 0.0
+    for s in range(6):
+        committed = T.tasc_session_get_tokens(rig.session, 0)
+        d = ON.draft(ref_tables, committed, cfg.k, cfg.lambda_q16, cfg.p_min_ctx)
+        d_dev = torch.tensor([d], dtype=torch.int32, device="cuda")
+        T.tasc_verify_step(rig.model, rig.session, d_dev, cfg.k, acc_d, emit_d, logits)
+        z = om.forward([int(committed[-1])] + d, cache)
+        got = logits.cpu().numpy()[0].astype(np.float64)
+        worst = max(worst, float(np.abs(got - z).max()))
+        a = OM.argmax_lowest(z)
+        m = OM.accept_length(d, a)
+        assert int(acc_d.cpu()[0]) == m
+        assert emit_d.cpu().numpy()[0].tolist() == d[:m] + [int(a[m])] + [-1] * (cfg.k - m)
+        cache.length += m + 1
+    print(f"max |logit - oracle| = {worst:.3e}", flush=True)
+    assert worst <= 1e-3
+
+
+@pytest.mark.parametrize("variant", ["f32_gqa_batch", "bf16_gqa_batch"])
+def test_small_batched_models(variant):
+    """Ragged prompts, batch > 1, GQA, several KV pages and a prompt longer than one chunk; both dtypes."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    base = W.get_config("cfg1")
+    cfg = base.scaled(dtype="f32" if variant.startswith("f32") else "bf16", n_layers=3, d_model=192, n_heads=6, n_kv_heads=2,
+                      head_dim=32, d_ffn=320, vocab=1000, batch=5, prompt_len=45, gen_len=40, k=5, n_docs=1500, n_max=4)
+    rig = Rig(cfg, max_rows=16)
+    tol = 1e-3 if cfg.dtype == "f32" else 5e-2
+    ref_tables = ON.build_tables_flat(rig.corpus[0], rig.corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
+    om = OM.OracleModel(cfg, rig.weights)
+    # ragged prompts
+    lens = [45, 1, 16, 33, 17]
+    rng = np.random.default_rng(1)
+    prompts = [rng.integers(0, cfg.vocab, n).astype(np.int32) for n in lens]
+    rig.prompts = np.concatenate(prompts)
+    rig.prompt_off = np.cumsum([0] + lens).astype(np.int64)
+    out, st, tr = rig.generate(trace_steps=cfg.gen_len)
+    g_out, g_st, _ = rig.generate(k=0)
+    assert (out == g_out).all(), "speculative output differs from the GPU's own greedy decode"
+    assert g_st.steps == cfg.gen_len - 1 and st.steps <= g_st.steps
+    for b in range(cfg.batch):
+        _replay(cfg, ref_tables, prompts[b].tolist(), tr[:, b], cfg.k, cfg.lambda_q16, cfg.p_min_ctx, out[b])
+    # logits: the oracle follows the GPU's committed tokens for a few steps
+    T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+    caches = []
+    for b in range(cfg.batch):
+        c = om.new_cache(rig.max_len)
+        z = om.forward(prompts[b].tolist(), c, last_only=True)
+        c.length = lens[b]
+        caches.append(c)
+        first = T.tasc_session_get_tokens(rig.session, b)[-1]
+        top2 = np.sort(z[0])[-2:]
+        assert first == int(np.argmax(z[0])) or top2[1] - top2[0] < 2 * tol
+    logits = torch.zeros((cfg.batch, cfg.k + 1, cfg.vocab), dtype=torch.float32, device="cuda")
+    drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+    worst = 0.0
+    for s in range(4):
+        T.tasc_draft(rig.ng, rig.session, rig.params(), drafts)
+        before = [T.tasc_session_get_tokens(rig.session, b) for b in range(cfg.batch)]
+        T.tasc_verify_step(rig.model, rig.session, drafts, cfg.k, None, None, logits)
+        got = logits.cpu().numpy().astype(np.float64)
+        d = drafts.cpu().numpy()
+        for b in range(cfg.batch):
+            z = om.forward([int(before[b][-1])] + d[b].tolist(), caches[b])
+            worst = max(worst, float(np.abs(got[b] - z).max()))
+            after = T.tasc_session_get_tokens(rig.session, b)
+            caches[b].length += len(after) - len(before[b])
+    print(f"{variant}: max |logit - oracle| = {worst:.3e}", flush=True)
+    assert worst <= tol
+
+
+def test_api_errors():
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    cfg = W.get_config("cfg1").scaled(n_docs=100, gen_len=8, prompt_len=8)
+    rig = Rig(cfg, max_rows=8)
+    drafts = torch.zeros((1, 4), dtype=torch.int32, device="cuda")
+    with pytest.raises(T.TascError) as e:                     # verify before prefill
+        T.tasc_verify_step(rig.model, rig.session, drafts, 4)
+    assert e.value.status == -4
+    with pytest.raises(T.TascError) as e:
+        T.tasc_draft(rig.ng, rig.session, rig.params(), drafts)
+    assert e.value.status == -4
+    bad = rig.prompts.copy()
+    bad[3] = cfg.vocab
+    with pytest.raises(T.TascError) as e:
+        T.tasc_session_prefill(rig.model, rig.session, bad, rig.prompt_off, 8)
+    assert e.value.status == -1
+    with pytest.raises(T.TascError) as e:                     # does not fit max_len
+        T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, 1000)
+    assert e.value.status == -1
+    T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, 8)
+    for k in (-1, 8, 16):
+        with pytest.raises(T.TascError) as e:
+            T.tasc_verify_step(rig.model, rig.session, drafts, k)
+        assert e.value.status == -1
+    with pytest.raises(T.TascError):
+        T.tasc_draft(rig.ng, rig.session, T.spec_params(4, 70000), drafts)
+    import ctypes                                             # workspace too small
+    out = ctypes.c_void_p()
+    rc = T.lib().tasc_session_create(rig.model.handle, 1, rig.max_len, 8, rig.session._kv_pool.data_ptr(), 16,
+                                     rig.session._workspace.data_ptr(), 16, ctypes.byref(out))
+    assert rc == -2 and out.value is None
+    # a draft outside the vocabulary is simply rejected
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    T.tasc_verify_step(rig.model, rig.session, torch.tensor([[10**6, 1, 2, 3]], dtype=torch.int32, device="cuda"), 4, acc)
+    assert int(acc.cpu()[0]) == 0
