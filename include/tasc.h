@@ -244,6 +244,33 @@ tasc_status tasc_generate(const tasc_model* m, const tasc_ngram* ng, tasc_sessio
 tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* tokens, int32_t cap,
                                     int32_t* n, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement: per-kernel-class device time, taken with HIP event pairs recorded on the stream
+ * each kernel is launched on.  Off by default (no events are recorded).  The classes follow the
+ * steps of the hot path: table build is timed by tasc_ngram_get_stats, the rest here.
+ * ---------------------------------------------------------------------------------------- */
+enum {
+    TASC_KC_DRAFT = 0,    /* draft proposal kernel                                            */
+    TASC_KC_PREPARE = 1,  /* row metadata + embedding gather                                  */
+    TASC_KC_NORM = 2,     /* RMSNorm                                                          */
+    TASC_KC_GEMM_QKV = 3, /* fused q/k/v projection                                           */
+    TASC_KC_ROPE_KV = 4,  /* RoPE + KV append                                                 */
+    TASC_KC_ATTN = 5,     /* attention over the paged cache                                   */
+    TASC_KC_GEMM_O = 6,   /* output projection + residual                                     */
+    TASC_KC_GEMM_GU = 7,  /* gate/up projection + SwiGLU                                      */
+    TASC_KC_GEMM_D = 8,   /* down projection + residual                                       */
+    TASC_KC_LMHEAD = 9,   /* LM head + bias + partial argmax                                  */
+    TASC_KC_ACCEPT = 10,  /* argmax reduce, draft compare, accept length, KV rollback         */
+    TASC_KC_VERIFY = 11,  /* one whole verify step (all of the above but the draft)           */
+    TASC_KC_LAYERS = 12,  /* the fused decoder-layer kernel of the small-batch verify step     */
+    TASC_N_KERNEL_CLASSES = 13
+};
+/* class_mask: bit c enables class c; 0 disables.  Applies to later calls of this process. */
+tasc_status tasc_profile_enable(uint32_t class_mask);
+/* Waits for the device, then returns and clears the time and launch count recorded per class.
+ * total_ms, launches: HOST arrays of TASC_N_KERNEL_CLASSES entries. */
+tasc_status tasc_profile_read(double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,8 +21,10 @@ EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
     "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
-    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens",
+    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read",
 ]
+KERNEL_CLASSES = ["draft", "prepare", "norm", "gemm_qkv", "rope_kv", "attn", "gemm_o", "gemm_gu", "gemm_d", "lmhead", "accept",
+                  "verify", "layers"]
 
 
 class TascError(RuntimeError):
@@ -92,6 +94,8 @@ def lib():
         L.tasc_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.POINTER(SpecParams), C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(GenStats), C.c_void_p]
         L.tasc_session_get_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
+        L.tasc_profile_enable.argtypes = [C.c_uint32]
+        L.tasc_profile_read.argtypes = [C.c_void_p, C.c_void_p]
         for name in ("tasc_ngram_destroy", "tasc_model_destroy", "tasc_session_destroy"):
             getattr(L, name).argtypes = [C.c_void_p]
             getattr(L, name).restype = None
@@ -289,3 +293,20 @@ def tasc_session_get_tokens(s: Session, b: int, stream=None) -> np.ndarray:
     buf = np.zeros(s.max_len, dtype=np.int32)
     _check(lib().tasc_session_get_tokens(s.handle, b, _ptr(buf), s.max_len, C.byref(n), _stream(stream)))
     return buf[:n.value].copy()
+
+
+def tasc_profile_enable(classes):
+    """classes: iterable of names from KERNEL_CLASSES (empty = off)."""
+    mask = 0
+    for c in classes:
+        mask |= 1 << KERNEL_CLASSES.index(c)
+    _check(lib().tasc_profile_enable(mask))
+
+
+def tasc_profile_read():
+    """Returns {class name: (total_ms, launches)} for the classes that recorded something, and clears."""
+    n = len(KERNEL_CLASSES)
+    ms = np.zeros(n, dtype=np.float64)
+    cnt = np.zeros(n, dtype=np.int64)
+    _check(lib().tasc_profile_read(_ptr(ms), _ptr(cnt)))
+    return {KERNEL_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}

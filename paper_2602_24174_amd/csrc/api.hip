@@ -448,13 +448,17 @@ tasc_status verify_step_impl(const tasc_model* m, tasc_session* s, const int32_t
                              int32_t* emitted, float* logits_dbg, int32_t* trace_step, hipStream_t st) {
     const int B = s->batch, nq = k + 1;
     TascSessDev& d = s->d;
+    TascProfScope whole(TASC_KC_VERIFY, st);
     k_prepare_verify<<<dim3((B * nq + 255) / 256), dim3(256), 0, st>>>(B, k, s->max_len, m->desc.vocab, d.tokens, d.n_tok, d.cached,
                                                                        drafts, d.row_tok, d.n_rows, d.pos0, d.sel_rows, d.sel_tok);
     TASC_LAUNCH_CHECK();
     tasc_status rc = tasc_forward_rows(m, s, nq, B * nq, logits_dbg, st);
     if (rc != TASC_OK) return rc;
-    k_accept<<<dim3((B + 63) / 64), dim3(64), 0, st>>>(B, k, s->max_len, s->max_new, drafts, d.amax, d.tokens, d.n_tok, d.cached,
-                                                       d.n_emit, d.counters, accept_len, emitted, trace_step);
+    {
+        TascProfScope ps(TASC_KC_ACCEPT, st);
+        k_accept<<<dim3((B + 63) / 64), dim3(64), 0, st>>>(B, k, s->max_len, s->max_new, drafts, d.amax, d.tokens, d.n_tok,
+                                                           d.cached, d.n_emit, d.counters, accept_len, emitted, trace_step);
+    }
     TASC_LAUNCH_CHECK();
     return TASC_OK;
 }

@@ -198,7 +198,10 @@ extern "C" tasc_status tasc_draft(const tasc_ngram* ng, tasc_session* s, const t
     a.p_min_ctx = p->p_min_ctx;
     a.ctx_gen = p->ctx_includes_generated;
     a.drafts = drafts;
-    k_draft<<<dim3(s->batch), dim3(kThreads), 0, (hipStream_t)stream>>>(a);
+    {
+        TascProfScope ps(TASC_KC_DRAFT, (hipStream_t)stream);
+        k_draft<<<dim3(s->batch), dim3(kThreads), 0, (hipStream_t)stream>>>(a);
+    }
     TASC_LAUNCH_CHECK();
     return TASC_OK;
 }

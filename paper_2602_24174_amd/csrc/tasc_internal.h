@@ -176,3 +176,14 @@ struct tasc_session {
 // forward.hip
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel,
                               float* logits_dbg, hipStream_t st);
+
+// profile.hip: optional event timing per kernel class
+bool tasc_prof_on(int cls);
+int tasc_prof_begin(int cls, hipStream_t st);
+void tasc_prof_end(int handle, hipStream_t st);
+struct TascProfScope {
+    int h;
+    hipStream_t st;
+    TascProfScope(int cls, hipStream_t s) : h(-1), st(s) { if (tasc_prof_on(cls)) h = tasc_prof_begin(cls, s); }
+    ~TascProfScope() { if (h >= 0) tasc_prof_end(h, st); }
+};
