@@ -245,6 +245,16 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
                                     int32_t* n, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Library-wide options (for tests and tuning; the defaults are what the benchmarks run).
+ *   TASC_CFG_SMALL_PATH  how a bf16 forward of at most 16 rows runs: 2 (default) = one persistent
+ *                        kernel for the whole step, 1 = the same kernel launched once per phase,
+ *                        0 = the type-generic kernels.  Results of 1 and 2 are bit-identical.
+ *   TASC_CFG_SMALL_GRID  workgroups of the persistent kernel; 0 (default) = one per compute unit.
+ * ---------------------------------------------------------------------------------------- */
+enum { TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1 };
+tasc_status tasc_config_set(int32_t key, int32_t value);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement: per-kernel-class device time, taken with HIP event pairs recorded on the stream
  * each kernel is launched on.  Off by default (no events are recorded).  The classes follow the
  * steps of the hot path: table build is timed by tasc_ngram_get_stats, the rest here.

@@ -192,6 +192,7 @@ extern "C" tasc_status tasc_model_create(const tasc_model_desc* desc, const tasc
     if ((rc = dev_copy(w->embed, (size_t)c.vocab * D * es, &m->embed)) != TASC_OK) return rc;
     if ((rc = dev_copy(w->lm_head, (size_t)c.vocab * D * es, &m->lm_head)) != TASC_OK) return rc;
     if ((rc = dev_copy(w->gf, D * 4, (void**)&m->gf)) != TASC_OK) return rc;
+    m->d_layers = nullptr;
     m->layers.resize(c.n_layers);
     for (int l = 0; l < c.n_layers; ++l) {
         TASC_REQUIRE(w->wq[l] && w->wk[l] && w->wv[l] && w->wo[l] && w->wg[l] && w->wu[l] && w->wd[l] && w->g1[l] && w->g2[l],
@@ -218,6 +219,7 @@ extern "C" tasc_status tasc_model_create(const tasc_model_desc* desc, const tasc
         if ((rc = dev_copy(w->g2[l], D * 4, &p)) != TASC_OK) return rc;
         L.g2 = (const float*)p;
     }
+    if ((rc = dev_copy(m->layers.data(), sizeof(TascLayerW) * c.n_layers, (void**)&m->d_layers)) != TASC_OK) return rc;
     // RoPE table: angle(p, i) = p * theta^(-2i/hd), double on the host, fp32 on the device
     {
         const int half = c.head_dim / 2;
@@ -333,6 +335,7 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     s->page_elems = 2 * (size_t)m->desc.n_kv_heads * TASC_KV_BLOCK * m->desc.head_dim;
     s->kv_layer_stride = (size_t)batch * s->max_blocks * s->page_elems;
     s->host_counters = nullptr;
+    s->bar_base = 0;
     char* w = (char*)workspace;
     int i = 0;
     TascSessDev& d = s->d;
@@ -365,6 +368,8 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     k_init_block_tab<<<dim3((n + 255) / 256), dim3(256), 0, 0>>>(batch, s->max_blocks, d.block_tab);
     TASC_LAUNCH_CHECK();
     TASC_HIP(hipMemsetAsync(d.counters, 0, 32 * sizeof(u64), 0));
+    // the MFMA attention multiplies masked keys by zero weights: the pool must never hold NaN or Inf patterns
+    TASC_HIP(hipMemsetAsync(kv_pool, 0, need_kv, 0));
     TASC_HIP(hipDeviceSynchronize());
     guard.p = nullptr;
     *out = s;
@@ -413,6 +418,7 @@ extern "C" tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s
     k_reset<<<dim3(B), dim3(256), 0, st>>>(B, s->max_len, d_prompts, d_off, d.tokens, d.n_tok, d.n_prompt, d.cached, d.n_emit,
                                            d.counters);
     TASC_LAUNCH_CHECK();
+    s->bar_base = 0;   // k_reset cleared the grid-barrier counter with the other counters
     k_check_prompts<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(d_prompts, total, m->desc.vocab, &d.counters[31]);
     TASC_LAUNCH_CHECK();
     TASC_HIP(hipMemcpyAsync(s->host_counters, d.counters, 32 * 8, hipMemcpyDeviceToHost, st));
@@ -431,7 +437,7 @@ extern "C" tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s
         k_prepare_prefill<<<dim3(B), dim3(64), 0, st>>>(B, C, c, s->max_len, d.tokens, d.n_prompt, d.row_tok, d.n_rows, d.pos0,
                                                         d.sel_rows, d.sel_tok);
         TASC_LAUNCH_CHECK();
-        tasc_status rc = tasc_forward_rows(m, s, C, any_last ? B : 0, nullptr, st);
+        tasc_status rc = tasc_forward_rows(m, s, C, any_last ? B : 0, nullptr, nullptr, st);
         if (rc != TASC_OK) return rc;
         k_commit_prefill<<<dim3((B + 63) / 64), dim3(64), 0, st>>>(B, C, c, s->max_len, max_new, d.n_prompt, d.sel_rows, d.amax,
                                                                    any_last ? 1 : 0, d.tokens, d.n_tok, d.cached, d.n_emit,
@@ -452,9 +458,10 @@ tasc_status verify_step_impl(const tasc_model* m, tasc_session* s, const int32_t
     k_prepare_verify<<<dim3((B * nq + 255) / 256), dim3(256), 0, st>>>(B, k, s->max_len, m->desc.vocab, d.tokens, d.n_tok, d.cached,
                                                                        drafts, d.row_tok, d.n_rows, d.pos0, d.sel_rows, d.sel_tok);
     TASC_LAUNCH_CHECK();
-    tasc_status rc = tasc_forward_rows(m, s, nq, B * nq, logits_dbg, st);
+    TascVerifyTail tail{k, drafts, accept_len, emitted, trace_step, false};
+    tasc_status rc = tasc_forward_rows(m, s, nq, B * nq, logits_dbg, &tail, st);
     if (rc != TASC_OK) return rc;
-    {
+    if (!tail.done) {
         TascProfScope ps(TASC_KC_ACCEPT, st);
         k_accept<<<dim3((B + 63) / 64), dim3(64), 0, st>>>(B, k, s->max_len, s->max_new, drafts, d.amax, d.tokens, d.n_tok,
                                                            d.cached, d.n_emit, d.counters, accept_len, emitted, trace_step);
@@ -523,6 +530,10 @@ extern "C" tasc_status tasc_generate(const tasc_model* m, const tasc_ngram* ng, 
     TASC_HIP(hipEventRecord(ev.e[2], st));
     TASC_HIP(hipMemcpyAsync(s->host_counters, d.counters, 32 * 8, hipMemcpyDeviceToHost, st));
     TASC_HIP(hipStreamSynchronize(st));
+    if (s->host_counters[TASC_CTR_BAR_ERR] != 0) {
+        tasc_set_error("generate: a grid barrier of the persistent kernel timed out; the session must be prefilled again");
+        return TASC_EHIP;
+    }
     if (stats) {
         memset(stats, 0, sizeof *stats);
         stats->steps = steps;

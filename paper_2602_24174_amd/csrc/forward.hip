@@ -2,13 +2,36 @@
 // LM head with fused bias and argmax.  Used by the prompt forward (nq = chunk length) and by the
 // verify step (nq = k + 1; paper, subsection "Speculative Decoding": the drafted tokens are verified
 // in parallel via a single forward pass).
+//
+// Which kernels run depends on the model and the session only (dtype, row count of the call), never on
+// data, so plain greedy decoding (k = 0) and speculative decoding of the same session shapes reduce
+// every row in the same order.
 #include "tasc_internal.h"
 #include "kernels_generic.h"
+#include "kernels_small.h"
+
+TascConfig g_tasc_config = {2, 0};
+
+extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
+    if (key == TASC_CFG_SMALL_PATH) {
+        TASC_REQUIRE(value >= 0 && value <= 2, "config_set: small path %d outside [0, 2]", value);
+        g_tasc_config.small_path = value;
+    } else if (key == TASC_CFG_SMALL_GRID) {
+        TASC_REQUIRE(value >= 0 && value <= 4096, "config_set: grid %d outside [0, 4096]", value);
+        g_tasc_config.small_grid = value;
+    } else {
+        tasc_set_error("config_set: unknown key %d", key);
+        return TASC_EINVAL;
+    }
+    return TASC_OK;
+}
 
 namespace {
 
+#define PROF(cls) TascProfScope _ps(cls, st)
+
 template <typename T>
-tasc_status forward_rows_t(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
+tasc_status forward_generic(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
     const int M = s->batch * nq;
@@ -16,44 +39,153 @@ tasc_status forward_rows_t(const tasc_model* m, tasc_session* s, int nq, int n_s
     const int nqkv = (H + 2 * Hkv) * hd, nqo = H * hd;
     KvGeom gm{H, Hkv, hd, nq, s->max_blocks, s->page_elems};
     const float scale = 1.0f / sqrtf((float)hd);
-
-    { TascProfScope ps(TASC_KC_PREPARE, st); k_embed<T><<<dim3(M), dim3(64), 0, st>>>((const T*)m->embed, d.row_tok, D, d.x); }
+    {
+        PROF(TASC_KC_PREPARE);
+        k_embed<T><<<dim3(M), dim3(64), 0, st>>>((const T*)m->embed, d.row_tok, D, d.x);
+    }
     TASC_LAUNCH_CHECK();
     for (int l = 0; l < c.n_layers; ++l) {
         const TascLayerW& w = m->layers[l];
         T* kv_layer = (T*)s->kv_pool + (size_t)l * s->kv_layer_stride;
-        { TascProfScope ps(TASC_KC_NORM, st); k_rmsnorm<T><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (T*)d.h); }
-        { TascProfScope ps(TASC_KC_GEMM_QKV, st); k_gemm_generic<T, EPI_STORE><<<dim3((nqkv + 3) / 4), dim3(256), 0, st>>>((const T*)d.h, (const T*)w.wqkv, M, nqkv, D,
-                                                                              d.qkv, nullptr); }
-        { TascProfScope ps(TASC_KC_ROPE_KV, st); k_rope_kv<T><<<dim3(M), dim3(256), 0, st>>>(d.qkv, m->rope_cos, m->rope_sin, c.max_pos, d.n_rows, d.pos0, d.block_tab,
-                                                  gm, (T*)d.q, kv_layer); }
-        { TascProfScope ps(TASC_KC_ATTN, st); k_attn_generic<T><<<dim3(s->batch, H), dim3(256), (size_t)nq * hd * sizeof(float), st>>>(
-            (const T*)d.q, kv_layer, d.n_rows, d.pos0, d.block_tab, gm, scale, (T*)d.att); }
-        { TascProfScope ps(TASC_KC_GEMM_O, st); k_gemm_generic<T, EPI_RESID><<<dim3((D + 3) / 4), dim3(256), 0, st>>>((const T*)d.att, (const T*)w.wo, M, D, nqo, d.x,
-                                                                          nullptr); }
-        { TascProfScope ps(TASC_KC_NORM, st); k_rmsnorm<T><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (T*)d.h); }
-        { TascProfScope ps(TASC_KC_GEMM_GU, st); k_gemm_generic<T, EPI_SWIGLU><<<dim3((F + 3) / 4), dim3(256), 0, st>>>((const T*)d.h, (const T*)w.wgu, M, F, D, nullptr,
-                                                                           (T*)d.act); }
-        { TascProfScope ps(TASC_KC_GEMM_D, st); k_gemm_generic<T, EPI_RESID><<<dim3((D + 3) / 4), dim3(256), 0, st>>>((const T*)d.act, (const T*)w.wd, M, D, F, d.x,
-                                                                          nullptr); }
+        {
+            PROF(TASC_KC_NORM);
+            k_rmsnorm<T><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (T*)d.h);
+        }
+        {
+            PROF(TASC_KC_GEMM_QKV);
+            k_gemm_generic<T, EPI_STORE><<<dim3((nqkv + 3) / 4), dim3(256), 0, st>>>((const T*)d.h, (const T*)w.wqkv, M, nqkv, D,
+                                                                                  d.qkv, nullptr);
+        }
+        {
+            PROF(TASC_KC_ROPE_KV);
+            k_rope_kv<T><<<dim3(M), dim3(256), 0, st>>>(d.qkv, m->rope_cos, m->rope_sin, c.max_pos, d.n_rows, d.pos0, d.block_tab,
+                                                      gm, (T*)d.q, kv_layer);
+        }
+        {
+            PROF(TASC_KC_ATTN);
+            k_attn_generic<T><<<dim3(s->batch, H), dim3(256), (size_t)nq * hd * sizeof(float), st>>>(
+                (const T*)d.q, kv_layer, d.n_rows, d.pos0, d.block_tab, gm, scale, (T*)d.att);
+        }
+        {
+            PROF(TASC_KC_GEMM_O);
+            k_gemm_generic<T, EPI_RESID><<<dim3((D + 3) / 4), dim3(256), 0, st>>>((const T*)d.att, (const T*)w.wo, M, D, nqo, d.x,
+                                                                              nullptr);
+        }
+        {
+            PROF(TASC_KC_NORM);
+            k_rmsnorm<T><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (T*)d.h);
+        }
+        {
+            PROF(TASC_KC_GEMM_GU);
+            k_gemm_generic<T, EPI_SWIGLU><<<dim3((F + 3) / 4), dim3(256), 0, st>>>((const T*)d.h, (const T*)w.wgu, M, F, D, nullptr,
+                                                                               (T*)d.act);
+        }
+        {
+            PROF(TASC_KC_GEMM_D);
+            k_gemm_generic<T, EPI_RESID><<<dim3((D + 3) / 4), dim3(256), 0, st>>>((const T*)d.act, (const T*)w.wd, M, D, F, d.x,
+                                                                              nullptr);
+        }
         TASC_LAUNCH_CHECK();
     }
     if (n_sel > 0) {
-        { TascProfScope ps(TASC_KC_NORM, st); k_rmsnorm<T><<<dim3(n_sel), dim3(64), 0, st>>>(d.x, m->gf, d.sel_rows, D, c.rms_eps, (T*)d.h); }
+        {
+            PROF(TASC_KC_NORM);
+            k_rmsnorm<T><<<dim3(n_sel), dim3(64), 0, st>>>(d.x, m->gf, d.sel_rows, D, c.rms_eps, (T*)d.h);
+        }
         BiasCsr bias{m->bias_rowptr, m->bias_col, m->bias_val, m->bias_base};
-        { TascProfScope ps(TASC_KC_LMHEAD, st); k_lmhead_generic<T><<<dim3(s->n_strips), dim3(256), 0, st>>>((const T*)d.h, (const T*)m->lm_head, d.sel_tok, n_sel,
-                                                                  c.vocab, D, bias, d.part_val, d.part_idx, s->n_strips,
-                                                                  logits_dbg); }
-        { TascProfScope ps(TASC_KC_ACCEPT, st); k_argmax_reduce<<<dim3(n_sel), dim3(64), 0, st>>>(d.part_val, d.part_idx, s->n_strips, d.amax); }
+        {
+            PROF(TASC_KC_LMHEAD);
+            k_lmhead_generic<T><<<dim3(s->n_strips), dim3(256), 0, st>>>((const T*)d.h, (const T*)m->lm_head, d.sel_tok, n_sel,
+                                                                      c.vocab, D, bias, d.part_val, d.part_idx, s->n_strips,
+                                                                      logits_dbg);
+        }
+        {
+            PROF(TASC_KC_ACCEPT);
+            k_argmax_reduce<<<dim3(n_sel), dim3(64), 0, st>>>(d.part_val, d.part_idx, s->n_strips, d.amax);
+        }
         TASC_LAUNCH_CHECK();
     }
+    return TASC_OK;
+}
+
+// the fused small-batch kernel serves a bf16 forward of at most 16 rows with these shapes
+bool small_path_fits(const tasc_model_desc& c, int batch, int nq) {
+    return c.dtype == TASC_BF16 && batch * nq <= SMALL_ROWS && c.d_model <= SMALL_KC && c.d_model % 32 == 0 &&
+           (c.head_dim == 32 || c.head_dim == 64 || c.head_dim == 128) && c.d_ffn % 32 == 0 && c.vocab >= 16 &&
+           (nq * (c.n_heads / c.n_kv_heads)) >= 1;
+}
+
+int g_cu_count = 0;
+
+tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, TascVerifyTail* tail,
+                          hipStream_t st) {
+    const tasc_model_desc& c = m->desc;
+    const TascSessDev& d = s->d;
+    if (g_cu_count == 0) {
+        int dev = 0, cus = 0;
+        TASC_HIP(hipGetDevice(&dev));
+        TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        int per_cu = 0;
+        TASC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_small_step, SMALL_THREADS, 0));
+        if (cus < 1 || per_cu < 1) {
+            tasc_set_error("forward: the persistent kernel does not fit the device (%d compute units, %d blocks each)", cus, per_cu);
+            return TASC_EHIP;
+        }
+        g_cu_count = cus;
+    }
+    SmallArgs a;
+    a.layers = m->d_layers;
+    a.embed = (const BF16*)m->embed;
+    a.lm_head = (const BF16*)m->lm_head;
+    a.gf = m->gf;
+    a.rope_cos = m->rope_cos;
+    a.rope_sin = m->rope_sin;
+    a.bias = BiasCsr{m->bias_rowptr, m->bias_col, m->bias_val, m->bias_base};
+    a.n_layers = c.n_layers; a.D = c.d_model; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim; a.F = c.d_ffn;
+    a.V = c.vocab; a.max_pos = c.max_pos; a.eps = c.rms_eps; a.scale = 1.0f / sqrtf((float)c.head_dim);
+    a.kv_pool = (BF16*)s->kv_pool; a.kv_layer_stride = s->kv_layer_stride; a.page_elems = s->page_elems;
+    a.B = s->batch; a.nq = nq; a.M = s->batch * nq; a.max_blocks = s->max_blocks; a.max_len = s->max_len;
+    a.n_strips = s->n_strips; a.max_new = s->max_new;
+    a.row_tok = d.row_tok; a.n_rows = d.n_rows; a.pos0 = d.pos0; a.block_tab = d.block_tab; a.sel_rows = d.sel_rows;
+    a.sel_tok = d.sel_tok; a.n_sel = n_sel;
+    a.x = d.x; a.q = (BF16*)d.q; a.att = (BF16*)d.att; a.act = (BF16*)d.act;
+    a.part_val = d.part_val; a.part_idx = d.part_idx; a.amax = d.amax; a.logits_dbg = logits_dbg;
+    a.k = tail ? tail->k : -1;
+    a.drafts = tail ? tail->drafts : nullptr;
+    a.tokens = d.tokens; a.n_tok = d.n_tok; a.cached = d.cached; a.n_emit = d.n_emit; a.counters = d.counters;
+    a.accept_len = tail ? tail->accept_len : nullptr;
+    a.emitted = tail ? tail->emitted : nullptr;
+    a.trace_step = tail ? tail->trace_step : nullptr;
+    a.bar_counter = &d.counters[TASC_CTR_BAR];
+    a.bar_error = (u32*)&d.counters[TASC_CTR_BAR_ERR];
+    const int n_phases = 3 + 5 * c.n_layers;
+    const int last = n_sel > 0 ? n_phases : n_phases - 2;   // without LM-head rows the step ends after the last layer
+    PROF(TASC_KC_LAYERS);
+    if (g_tasc_config.small_path == 2) {
+        int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
+        grid = grid < g_cu_count ? grid : g_cu_count;        // every workgroup must be resident: at most one per compute unit
+        a.bar_base = s->bar_base;
+        k_small_step<<<dim3(grid), dim3(SMALL_THREADS), 0, st>>>(a, 0, last);
+        s->bar_base += (u64)(last - 1) * grid;
+    } else {
+        a.bar_base = s->bar_base;
+        for (int ph = 0; ph < last; ++ph) {
+            // a launch of one phase crosses no barrier; the grid only needs to cover the phase's items
+            k_small_step<<<dim3(g_cu_count), dim3(SMALL_THREADS), 0, st>>>(a, ph, ph + 1);
+        }
+    }
+    TASC_LAUNCH_CHECK();
+    if (tail) tail->done = n_sel > 0;
     return TASC_OK;
 }
 
 }  // namespace
 
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel, float* logits_dbg,
-                              hipStream_t st) {
-    if (m->desc.dtype == TASC_F32) return forward_rows_t<float>(m, s, nq, n_sel, logits_dbg, st);
-    return forward_rows_t<BF16>(m, s, nq, n_sel, logits_dbg, st);
+                              TascVerifyTail* tail, hipStream_t st) {
+    if (tail) tail->done = false;
+    if (g_tasc_config.small_path != 0 && small_path_fits(m->desc, s->batch, nq))
+        return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);
+    if (m->desc.dtype == TASC_F32) return forward_generic<float>(m, s, nq, n_sel, logits_dbg, st);
+    return forward_generic<BF16>(m, s, nq, n_sel, logits_dbg, st);
 }

@@ -122,6 +122,7 @@ struct tasc_model {
     int32_t* bias_col;
     float* bias_val;
     float* bias_base;
+    TascLayerW* d_layers;   // device copy of `layers`
     std::vector<void*> allocs;
 };
 
@@ -171,11 +172,33 @@ struct tasc_session {
     size_t page_elems;        // elements per page (K and V)
     TascSessDev d;
     u64* host_counters;       // pinned
+    u64 bar_base;             // arrivals the grid-barrier counter (counters[24]) has seen so far
 };
+
+// counters[] slots used beyond the statistics
+#define TASC_CTR_BAR 24       // grid-barrier arrival counter
+#define TASC_CTR_BAR_ERR 25   // grid-barrier time-out flag (low 32 bits)
+
+// the tail of a verify step, fused into the forward when the small-batch kernel runs it
+struct TascVerifyTail {
+    int32_t k;
+    const int32_t* drafts;
+    int32_t* accept_len;
+    int32_t* emitted;
+    int32_t* trace_step;
+    bool done;                // out: the forward already performed the accept
+};
+
+// library-wide options (tasc_config_set)
+struct TascConfig {
+    int small_path;           // 0: generic kernels only, 1: fused kernel one phase per launch, 2: persistent
+    int small_grid;           // workgroups of the persistent kernel (0 = one per compute unit)
+};
+extern TascConfig g_tasc_config;
 
 // forward.hip
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel,
-                              float* logits_dbg, hipStream_t st);
+                              float* logits_dbg, TascVerifyTail* tail, hipStream_t st);
 
 // profile.hip: optional event timing per kernel class
 bool tasc_prof_on(int cls);

@@ -175,3 +175,64 @@ def test_api_errors():
     acc = torch.zeros(1, dtype=torch.int32, device="cuda")
     T.tasc_verify_step(rig.model, rig.session, torch.tensor([[10**6, 1, 2, 3]], dtype=torch.int32, device="cuda"), 4, acc)
     assert int(acc.cpu()[0]) == 0
+
+
+@pytest.mark.parametrize("heads", [(6, 2, 32), (4, 2, 64), (2, 1, 128), (4, 4, 64)])
+def test_small_batch_fused_kernel(heads):
+    """bf16 forwards of at most 16 rows run in the fused persistent kernel: against the oracle, against the
+    same kernel launched phase by phase (bit-identical), and speculative == greedy within each mode."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    H, Hkv, hd = heads
+    cfg = W.get_config("cfg1").scaled(dtype="bf16", n_layers=3, d_model=H * hd if H * hd >= 192 else 192, n_heads=H,
+                                      n_kv_heads=Hkv, head_dim=hd, d_ffn=320, vocab=1000, batch=2, prompt_len=70, gen_len=48,
+                                      k=6, n_docs=1500, n_max=4)
+    rig = Rig(cfg, max_rows=8)                     # prompt chunks of 8 rows x 2 sequences = 16 rows
+    lens = [70, 37]
+    rng = np.random.default_rng(7)
+    prompts = [rng.integers(0, cfg.vocab, n).astype(np.int32) for n in lens]
+    rig.prompts = np.concatenate(prompts)
+    rig.prompt_off = np.cumsum([0] + lens).astype(np.int64)
+    ref_tables = ON.build_tables_flat(rig.corpus[0], rig.corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
+    om = OM.OracleModel(cfg, rig.weights)
+    results = {}
+    try:
+        for mode in (2, 1, 0):
+            print(f"heads {heads} mode {mode}", flush=True)
+            T.tasc_config_set(T.TASC_CFG_SMALL_PATH, mode)
+            out, st, tr = rig.generate(trace_steps=cfg.gen_len)
+            g_out, g_st, _ = rig.generate(k=0)
+            assert (out == g_out).all(), f"mode {mode}: speculative output differs from greedy"
+            for b in range(cfg.batch):
+                _replay(cfg, ref_tables, prompts[b].tolist(), tr[:, b], cfg.k, cfg.lambda_q16, cfg.p_min_ctx, out[b])
+            # logits of a few verify steps
+            T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+            caches = []
+            for b in range(cfg.batch):
+                c = om.new_cache(rig.max_len)
+                om.forward(prompts[b].tolist(), c, last_only=True)
+                c.length = lens[b]
+                caches.append(c)
+            logits = torch.zeros((cfg.batch, cfg.k + 1, cfg.vocab), dtype=torch.float32, device="cuda")
+            drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+            worst, all_logits = 0.0, []
+            for s in range(5):
+                T.tasc_draft(rig.ng, rig.session, rig.params(), drafts)
+                before = [T.tasc_session_get_tokens(rig.session, b) for b in range(cfg.batch)]
+                T.tasc_verify_step(rig.model, rig.session, drafts, cfg.k, None, None, logits)
+                got = logits.cpu().numpy()
+                all_logits.append(got.copy())
+                d = drafts.cpu().numpy()
+                for b in range(cfg.batch):
+                    z = om.forward([int(before[b][-1])] + d[b].tolist(), caches[b])
+                    worst = max(worst, float(np.abs(got[b].astype(np.float64) - z).max()))
+                    after = T.tasc_session_get_tokens(rig.session, b)
+                    caches[b].length += len(after) - len(before[b])
+            print(f"mode {mode}: max |logit - oracle| = {worst:.3e}, steps {st.steps}", flush=True)
+            assert worst <= 5e-2
+            results[mode] = (out, tr, np.stack(all_logits))
+    finally:
+        T.tasc_config_set(T.TASC_CFG_SMALL_PATH, 2)
+    assert (results[1][0] == results[2][0]).all() and (results[1][1] == results[2][1]).all()
+    assert (results[1][2] == results[2][2]).all(), "persistent and per-phase launches must be bit-identical"
