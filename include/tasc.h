@@ -250,8 +250,12 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
  *                        kernel for the whole step, 1 = the same kernel launched once per phase,
  *                        0 = the type-generic kernels.  Results of 1 and 2 are bit-identical.
  *   TASC_CFG_SMALL_GRID  workgroups of the persistent kernel; 0 (default) = one per compute unit.
+ *   TASC_CFG_SMALL_LAYER_WGS, TASC_CFG_SMALL_LAYER_STRIDE
+ *                        the layer phases run on the workgroups stride * j, j < wgs, of that grid
+ *                        (0 = defaults); the LM head always uses the whole grid.  Results do not
+ *                        depend on these.
  * ---------------------------------------------------------------------------------------- */
-enum { TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1 };
+enum { TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3 };
 tasc_status tasc_config_set(int32_t key, int32_t value);
 
 /* ------------------------------------------------------------------------------------------
@@ -280,6 +284,12 @@ tasc_status tasc_profile_enable(uint32_t class_mask);
 /* Waits for the device, then returns and clears the time and launch count recorded per class.
  * total_ms, launches: HOST arrays of TASC_N_KERNEL_CLASSES entries. */
 tasc_status tasc_profile_read(double* total_ms, int64_t* launches);
+
+/* Per-phase timing of the persistent small-batch kernel: while device_buf is non-NULL every launch
+ * writes, for workgroup w < capacity / (2 * phases) and phase p (phases = 3 + 5 * n_layers: embedding,
+ * five per layer, LM head, accept), the 100 MHz wall-clock ticks at which w began and ended p into
+ * device_buf[(w * phases + p) * 2 + {0, 1}].  device_buf: DEVICE uint64[capacity]; NULL turns it off. */
+tasc_status tasc_profile_phases(uint64_t* device_buf, int64_t capacity);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
     "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
-    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set",
+    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set", "tasc_profile_phases",
 ]
 KERNEL_CLASSES = ["draft", "prepare", "norm", "gemm_qkv", "rope_kv", "attn", "gemm_o", "gemm_gu", "gemm_d", "lmhead", "accept",
                   "verify", "layers"]
@@ -95,6 +95,7 @@ def lib():
                                     C.POINTER(SpecParams), C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(GenStats), C.c_void_p]
         L.tasc_session_get_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
         L.tasc_config_set.argtypes = [C.c_int32, C.c_int32]
+        L.tasc_profile_phases.argtypes = [C.c_void_p, C.c_int64]
         L.tasc_profile_enable.argtypes = [C.c_uint32]
         L.tasc_profile_read.argtypes = [C.c_void_p, C.c_void_p]
         for name in ("tasc_ngram_destroy", "tasc_model_destroy", "tasc_session_destroy"):
@@ -313,8 +314,13 @@ def tasc_profile_read():
     return {KERNEL_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}
 
 
-TASC_CFG_SMALL_PATH, TASC_CFG_SMALL_GRID = 0, 1
+TASC_CFG_SMALL_PATH, TASC_CFG_SMALL_GRID, TASC_CFG_SMALL_LAYER_WGS, TASC_CFG_SMALL_LAYER_STRIDE = 0, 1, 2, 3
 
 
 def tasc_config_set(key: int, value: int):
     _check(lib().tasc_config_set(key, value))
+
+
+def tasc_profile_phases(buf):
+    """buf: cuda int64/uint64 tensor (or None to turn the per-phase timestamps off)."""
+    _check(lib().tasc_profile_phases(_ptr(buf), 0 if buf is None else buf.numel()))

@@ -282,6 +282,7 @@ WsLayout ws_layout(const tasc_model_desc& c, int B, int max_len, int max_rows) {
         M * n_strips * 4, M * n_strips * 4, M * 4,                   // part_val part_idx amax
         16,                                                          // att_part (reserved)
         (size_t)B * TASC_MAX_K * 4,                                  // drafts
+        M * (n_strips + 1) * 4,                                      // bias_ptr
     };
     WsLayout L;
     size_t o = 0;
@@ -336,6 +337,7 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     s->kv_layer_stride = (size_t)batch * s->max_blocks * s->page_elems;
     s->host_counters = nullptr;
     s->bar_base = 0;
+    s->barb_base = 0;
     char* w = (char*)workspace;
     int i = 0;
     TascSessDev& d = s->d;
@@ -362,6 +364,7 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     d.amax = (int32_t*)(w + L.off[i++]);
     d.att_part = (float*)(w + L.off[i++]);
     d.drafts = (int32_t*)(w + L.off[i++]);
+    d.bias_ptr = (int32_t*)(w + L.off[i++]);
     struct Guard { tasc_session* p; ~Guard() { if (p) tasc_session_destroy(p); } } guard{s};
     TASC_HIP(hipHostMalloc((void**)&s->host_counters, 32 * sizeof(u64), hipHostMallocDefault));
     const int n = batch * s->max_blocks;
@@ -418,7 +421,8 @@ extern "C" tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s
     k_reset<<<dim3(B), dim3(256), 0, st>>>(B, s->max_len, d_prompts, d_off, d.tokens, d.n_tok, d.n_prompt, d.cached, d.n_emit,
                                            d.counters);
     TASC_LAUNCH_CHECK();
-    s->bar_base = 0;   // k_reset cleared the grid-barrier counter with the other counters
+    s->bar_base = 0;   // k_reset cleared the grid-barrier counters with the other counters
+    s->barb_base = 0;
     k_check_prompts<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(d_prompts, total, m->desc.vocab, &d.counters[31]);
     TASC_LAUNCH_CHECK();
     TASC_HIP(hipMemcpyAsync(s->host_counters, d.counters, 32 * 8, hipMemcpyDeviceToHost, st));

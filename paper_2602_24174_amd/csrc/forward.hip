@@ -10,7 +10,16 @@
 #include "kernels_generic.h"
 #include "kernels_small.h"
 
-TascConfig g_tasc_config = {2, 0};
+TascConfig g_tasc_config = {2, 0, 0, 0};
+static u64* g_phase_ts = nullptr;
+static int64_t g_phase_ts_cap = 0;
+
+extern "C" tasc_status tasc_profile_phases(uint64_t* device_buf, int64_t capacity) {
+    TASC_REQUIRE(capacity >= 0 && (device_buf || capacity == 0), "profile_phases: bad buffer");
+    g_phase_ts = (u64*)device_buf;
+    g_phase_ts_cap = device_buf ? capacity : 0;
+    return TASC_OK;
+}
 
 extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
     if (key == TASC_CFG_SMALL_PATH) {
@@ -19,6 +28,12 @@ extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
     } else if (key == TASC_CFG_SMALL_GRID) {
         TASC_REQUIRE(value >= 0 && value <= 4096, "config_set: grid %d outside [0, 4096]", value);
         g_tasc_config.small_grid = value;
+    } else if (key == TASC_CFG_SMALL_LAYER_WGS) {
+        TASC_REQUIRE(value >= 0 && value <= 4096, "config_set: layer workgroups %d outside [0, 4096]", value);
+        g_tasc_config.layer_wgs = value;
+    } else if (key == TASC_CFG_SMALL_LAYER_STRIDE) {
+        TASC_REQUIRE(value >= 0 && value <= 64, "config_set: layer stride %d outside [0, 64]", value);
+        g_tasc_config.layer_stride = value;
     } else {
         tasc_set_error("config_set: unknown key %d", key);
         return TASC_EINVAL;
@@ -126,7 +141,13 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
         TASC_HIP(hipGetDevice(&dev));
         TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         int per_cu = 0;
-        TASC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_small_step, SMALL_THREADS, 0));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_small_step<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     SMALL_LDS_BYTES));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_small_step<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     SMALL_LDS_BYTES));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_small_step<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     SMALL_LDS_BYTES));
+        TASC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_small_step<4>, SMALL_THREADS, SMALL_LDS_BYTES));
         if (cus < 1 || per_cu < 1) {
             tasc_set_error("forward: the persistent kernel does not fit the device (%d compute units, %d blocks each)", cus, per_cu);
             return TASC_EHIP;
@@ -157,21 +178,40 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     a.emitted = tail ? tail->emitted : nullptr;
     a.trace_step = tail ? tail->trace_step : nullptr;
     a.bar_counter = &d.counters[TASC_CTR_BAR];
+    a.barb_counter = &d.counters[TASC_CTR_BARB];
     a.bar_error = (u32*)&d.counters[TASC_CTR_BAR_ERR];
-    const int n_phases = 3 + 5 * c.n_layers;
-    const int last = n_sel > 0 ? n_phases : n_phases - 2;   // without LM-head rows the step ends after the last layer
+    a.bias_ptr = d.bias_ptr;
+    const int n_phases = 3 + 5 * c.n_layers, n_lg_phases = 1 + 5 * c.n_layers;
+    a.phase_ts = g_phase_ts;
+    a.phase_ts_wgs = g_phase_ts ? (int32_t)(g_phase_ts_cap / (2 * (int64_t)n_phases)) : 0;
+    const int last = n_sel > 0 ? n_phases : n_lg_phases;   // without LM-head rows the step ends after the last layer
+    int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
+    grid = grid < g_cu_count ? grid : g_cu_count;            // every workgroup must be resident: at most one per compute unit
+    // layer group: by default the first 48 workgroups, which the dispatcher spreads over all XCDs (fewer
+    // participants make the barriers of the 150 latency-bound layer phases cheaper, and a phase has at most
+    // 96 work items anyway; the LM head uses the whole grid)
+    int stride = g_tasc_config.layer_stride > 0 ? g_tasc_config.layer_stride : 1;
+    int lg = g_tasc_config.layer_wgs > 0 ? g_tasc_config.layer_wgs : 48;
+    if (stride > grid) stride = grid;
+    if (lg > (grid + stride - 1) / stride) lg = (grid + stride - 1) / stride;
+    a.lg_stride = stride;
+    a.lg_count = lg;
+    a.bar_base = s->bar_base;
+    a.barb_base = s->barb_base;
     PROF(TASC_KC_LAYERS);
+    auto launch = [&](int p0, int p1) {
+        if (c.head_dim == 32) k_small_step<1><<<dim3(grid), dim3(SMALL_THREADS), SMALL_LDS_BYTES, st>>>(a, p0, p1);
+        else if (c.head_dim == 64) k_small_step<2><<<dim3(grid), dim3(SMALL_THREADS), SMALL_LDS_BYTES, st>>>(a, p0, p1);
+        else k_small_step<4><<<dim3(grid), dim3(SMALL_THREADS), SMALL_LDS_BYTES, st>>>(a, p0, p1);
+    };
     if (g_tasc_config.small_path == 2) {
-        int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
-        grid = grid < g_cu_count ? grid : g_cu_count;        // every workgroup must be resident: at most one per compute unit
-        a.bar_base = s->bar_base;
-        k_small_step<<<dim3(grid), dim3(SMALL_THREADS), 0, st>>>(a, 0, last);
-        s->bar_base += (u64)(last - 1) * grid;
+        launch(0, last);
+        s->bar_base += (u64)(n_lg_phases - 1) * lg;
+        s->barb_base += (u64)(last - n_lg_phases) * grid;
     } else {
-        a.bar_base = s->bar_base;
         for (int ph = 0; ph < last; ++ph) {
-            // a launch of one phase crosses no barrier; the grid only needs to cover the phase's items
-            k_small_step<<<dim3(g_cu_count), dim3(SMALL_THREADS), 0, st>>>(a, ph, ph + 1);
+            // a launch of one phase crosses no barrier
+            launch(ph, ph + 1);
         }
     }
     TASC_LAUNCH_CHECK();

@@ -3,7 +3,7 @@
 // A verify step of k+1 <= 16 rows streams every weight once and does almost no arithmetic, so its
 // time is set by launch and dependency latency, not by bandwidth or MFMA rate.  All phases of all
 // layers therefore run inside one launch of `k_small_step`: the grid stays resident (one workgroup
-// per compute unit at most) and moves from phase to phase through a grid-wide barrier.  Phases:
+// of 8 waves per compute unit at most) and moves from phase to phase through a grid-wide barrier.
 //   0                  embedding gather
 //   1 + 5l + 0         RMSNorm + fused q/k/v projection + RoPE + KV append
 //   1 + 5l + 1         attention of the rows over the paged cache (GQA group packed into the MFMA tile)
@@ -16,20 +16,34 @@
 //
 // GEMMs use v_mfma_f32_16x16x32_bf16 with the WEIGHT tile as the A operand (16 output features x 32 k)
 // and the 16 activation rows as the B operand, so a lane ends up with 4 consecutive output features
-// of one row.  Every row's reduction order is fixed by the kernel (k-steps dealt round-robin to the 4
-// waves, partial sums added in wave order), independent of how many rows are valid.
+// of one row.  Inside a phase everything that does not depend on the previous phase (weight tiles,
+// RoPE table entries, page addresses) is requested before the activations are staged, so that a phase
+// costs about one memory round trip.  Every row's reduction order is fixed by the kernel (k-steps dealt
+// round-robin to the 8 waves, partial sums added in wave order), independent of how many rows are valid.
 #pragma once
 #include "kernels_generic.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// eight bf16 values given as four packed 32-bit words, as an MFMA operand (no trip through memory)
+__device__ inline bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    return __builtin_bit_cast(bf16x8, u32x4{a, b, c, d});
+}
 
 #define SMALL_ROWS 16
 #define SMALL_KC 1536                 // activation columns staged in LDS at a time
 #define SMALL_KP (SMALL_KC + 8)       // padded LDS row length (elements)
-#define SMALL_THREADS 256
-#define SMALL_MAX_KS ((SMALL_KC / 32 + 3) / 4)   // k-steps of one chunk a wave can own
+#define SMALL_THREADS 512
+#define SMALL_NW 8                    // waves per workgroup
+#define SMALL_WKS 6                   // k-steps of one staged chunk a wave owns at most: KC / 32 / NW
+#define SMALL_ATT_SLOT 2048           // floats of one attention combine slot (rows of a pass x head_dim)
+
+// dynamic LDS layout (bytes)
+#define SMALL_LDS_ACT 0
+#define SMALL_LDS_RED (SMALL_ROWS * SMALL_KP * 2)                 // 49408
+#define SMALL_LDS_BYTES (SMALL_LDS_RED + 2 * SMALL_NW * 64 * 16)  // + 16384 = 65792
 
 struct SmallArgs {
     // model
@@ -72,73 +86,101 @@ struct SmallArgs {
     int32_t* accept_len;
     int32_t* emitted;
     int32_t* trace_step;
-    // grid barrier: monotone arrival counter, value it had when this launch began, error flag
-    u64* bar_counter;
+    // Two grid barriers, each a monotone arrival counter plus the value it had when this launch began.
+    // Barrier A joins the workgroups of the layer group (the embedding and layer phases), barrier B all
+    // workgroups of the grid (before the LM head and before the accept).
+    u64* bar_counter;       // A
     u64 bar_base;
+    u64* barb_counter;      // B
+    u64 barb_base;
     u32* bar_error;
+    // layer group: workgroups wg = lg_stride * j, j < lg_count, run the layer phases
+    int32_t lg_stride, lg_count;
+    // bias cursor table [n_sel][n_strips + 1]: entries of bias row sel_tok[r] with column < strip start
+    int32_t* bias_ptr;
+    // optional: wall-clock ticks [workgroup][phase][begin, end] of this launch (nullptr = off)
+    u64* phase_ts;
+    int32_t phase_ts_wgs;   // workgroups the buffer has room for
 };
 
 // ---------------------------------------------------------------- grid barrier
 // Every workgroup arrives once per barrier; the counter never resets (the host advances bar_base by
-// barriers * workgroups per launch).  The wait is bounded: on time-out the error flag is raised and
-// every later barrier falls through, so the grid always drains.
-__device__ inline void grid_sync(const SmallArgs& a, u32 index, u32 nwg) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+// barriers * workgroups per launch).  The workgroup barrier collects the waves' stores, then wave 0
+// alone publishes them (agent-scope release), arrives, waits, and acquires for the whole compute unit.
+// The wait is bounded: on time-out the error flag is raised and every later barrier falls through,
+// so the grid always drains.
+__device__ __noinline__ void grid_sync(u64* counter, u64 target, u32* error, int sleep) {
     __syncthreads();
-    if (threadIdx.x == 0) {
-        const u64 target = a.bar_base + (u64)(index + 1) * nwg;
-        __hip_atomic_fetch_add(a.bar_counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        u32 spins = 0;
-        while (__hip_atomic_load(a.bar_counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(2);
-            if ((++spins & 1023u) == 0) {
-                if (__hip_atomic_load(a.bar_error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
-                if (spins > (1u << 22)) {
-                    __hip_atomic_fetch_or(a.bar_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
+    if (threadIdx.x < 64) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        if (threadIdx.x == 0) {
+            __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            u32 spins = 0;
+            while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (sleep) __builtin_amdgcn_s_sleep(32); else __builtin_amdgcn_s_sleep(1);
+                if ((++spins & 1023u) == 0) {
+                    if (__hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+                    if (spins > (1u << 22)) {
+                        __hip_atomic_fetch_or(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
 // ---------------------------------------------------------------- staging of the 16 activation rows
-// s_act[r][0..kw) = bf16(x[r][kc0..] * rinv[r] * g[kc0..]) for r < M, zero for r >= M.
+// Wave w stages rows w and w + 8: s_act[r][0..D) = bf16(x[r] * g / sqrt(mean(x[r]^2) + eps)) for r < M, zero for
+// r >= M.  One pass: the row stays in registers between the sum of squares and the scaling.  D <= 1536.
 __device__ inline void stage_normed(const float* __restrict__ x, const float* __restrict__ g, const int32_t* __restrict__ sel,
-                                    int M, int D, float eps, int kc0, int kw, uint16_t* s_act, float* s_rinv) {
+                                    int M, int D, float eps, uint16_t* s_act) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (kc0 == 0) {
-        for (int r = wave; r < SMALL_ROWS; r += 4) {
-            float ss = 0.f;
-            if (r < M) {
-                int src = sel ? sel[r] : r;
-                if (src < 0) src = 0;
-                const float* xr = x + (size_t)src * D;
-                for (int k = lane * 4; k < D; k += 256) {
-                    float4 v = *reinterpret_cast<const float4*>(xr + k);
-                    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-                }
-            }
-            ss = wave_sum(ss);
-            if (lane == 0) s_rinv[r] = 1.0f / sqrtf(ss / (float)D + eps);
-        }
-        __syncthreads();
-    }
-    for (int idx = threadIdx.x; idx < SMALL_ROWS * (kw / 4); idx += SMALL_THREADS) {
-        const int r = idx / (kw / 4), k = (idx % (kw / 4)) * 4;
-        uint2 o = make_uint2(0, 0);
+    float4 v[2][6], gg[6];
+    float ss[2] = {0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 6; ++t)
+        if (4 * (lane + 64 * t) < D) gg[t] = *reinterpret_cast<const float4*>(g + 4 * (lane + 64 * t));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = wave + SMALL_NW * j;
         if (r < M) {
             int src = sel ? sel[r] : r;
             if (src < 0) src = 0;
-            const float4 v = *reinterpret_cast<const float4*>(x + (size_t)src * D + kc0 + k);
-            const float4 gg = *reinterpret_cast<const float4*>(g + kc0 + k);
-            const float ri = s_rinv[r];
-            o.x = (uint32_t)f2bf(v.x * ri * gg.x) | ((uint32_t)f2bf(v.y * ri * gg.y) << 16);
-            o.y = (uint32_t)f2bf(v.z * ri * gg.z) | ((uint32_t)f2bf(v.w * ri * gg.w) << 16);
+            const float* xr = x + (size_t)src * D;
+#pragma unroll
+            for (int t = 0; t < 6; ++t)
+                if (4 * (lane + 64 * t) < D) v[j][t] = *reinterpret_cast<const float4*>(xr + 4 * (lane + 64 * t));
         }
-        *reinterpret_cast<uint2*>(s_act + r * SMALL_KP + k) = o;
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if (wave + SMALL_NW * j < M) {
+#pragma unroll
+            for (int t = 0; t < 6; ++t)
+                if (4 * (lane + 64 * t) < D)
+                    ss[j] += v[j][t].x * v[j][t].x + v[j][t].y * v[j][t].y + v[j][t].z * v[j][t].z + v[j][t].w * v[j][t].w;
+        }
+        ss[j] = wave_sum(ss[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = wave + SMALL_NW * j;
+        const float ri = 1.0f / sqrtf(ss[j] / (float)D + eps);
+#pragma unroll
+        for (int t = 0; t < 6; ++t) {
+            const int k = 4 * (lane + 64 * t);
+            if (k < D) {
+                uint2 o = make_uint2(0, 0);
+                if (r < M) {
+                    o.x = (uint32_t)f2bf(v[j][t].x * ri * gg[t].x) | ((uint32_t)f2bf(v[j][t].y * ri * gg[t].y) << 16);
+                    o.y = (uint32_t)f2bf(v[j][t].z * ri * gg[t].z) | ((uint32_t)f2bf(v[j][t].w * ri * gg[t].w) << 16);
+                }
+                *reinterpret_cast<uint2*>(s_act + r * SMALL_KP + k) = o;
+            }
+        }
     }
     __syncthreads();
 }
@@ -154,53 +196,49 @@ __device__ inline void stage_copy(const BF16* __restrict__ src, int M, int K, in
     __syncthreads();
 }
 
-// ---------------------------------------------------------------- MFMA tiles
-// Adds to acc[t] the product of weight tile t (rows wrow[t] .. +16 of a [*, K] matrix, columns
-// kc0 .. kc0+kw) with the staged rows.  KSPLIT: the chunk's k-steps are dealt round-robin to the 4
-// waves (each wave then holds a partial sum); otherwise the calling wave does all of them.
-template <int NT, bool KSPLIT>
-__device__ inline void mfma_tiles(const BF16* const* wrow, int K, int kc0, int kw, const uint16_t* s_act, f32x4* acc) {
+// ---------------------------------------------------------------- MFMA tiles, k-steps dealt to the 8 waves
+// Weight fragments of the wave's k-steps (ks = wave, wave + 8, ... of a chunk of nks k-steps).
+template <int NT>
+__device__ inline void load_w(const BF16* const* wrow, int K, int kc0, int nks, bf16x8 (&w)[NT][SMALL_WKS]) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nks = kw / 32;
-    const int first = KSPLIT ? wave : 0, step = KSPLIT ? 4 : 1;
     const size_t woff = (size_t)(lane & 15) * K + kc0 + 8 * (lane >> 4);
-    const int aoff = (lane & 15) * SMALL_KP + 8 * (lane >> 4);
-    for (int ks0 = first; ks0 < nks; ks0 += step * 6) {
-        bf16x8 w[NT][6];
 #pragma unroll
-        for (int u = 0; u < 6; ++u) {
-            const int ks = ks0 + u * step;
-            if (ks < nks) {
+    for (int u = 0; u < SMALL_WKS; ++u) {
+        const int ks = wave + SMALL_NW * u;
+        if (ks < nks) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t) w[t][u] = *reinterpret_cast<const bf16x8*>(wrow[t] + woff + ks * 32);
-            }
+            for (int t = 0; t < NT; ++t) w[t][u] = *reinterpret_cast<const bf16x8*>(wrow[t] + woff + ks * 32);
         }
+    }
+}
+template <int NT>
+__device__ inline void mma_w(const bf16x8 (&w)[NT][SMALL_WKS], int nks, const uint16_t* s_act, f32x4* acc) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int aoff = (lane & 15) * SMALL_KP + 8 * (lane >> 4);
 #pragma unroll
-        for (int u = 0; u < 6; ++u) {
-            const int ks = ks0 + u * step;
-            if (ks < nks) {
-                const bf16x8 b = *reinterpret_cast<const bf16x8*>(s_act + aoff + ks * 32);
+    for (int u = 0; u < SMALL_WKS; ++u) {
+        const int ks = wave + SMALL_NW * u;
+        if (ks < nks) {
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(s_act + aoff + ks * 32);
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][u], b, acc[t], 0, 0, 0);
-            }
+            for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][u], b, acc[t], 0, 0, 0);
         }
     }
 }
 
-// Sums the 4 waves' partial tiles in wave order; the result is valid in wave 0.
+// Sums the waves' partial tiles in wave order; the result is valid in wave 0.
 template <int NT>
 __device__ inline void reduce_waves(f32x4* acc, f32x4* s_red) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) s_red[(t * 4 + wave) * 64 + lane] = acc[t];
+    for (int t = 0; t < NT; ++t) s_red[(t * SMALL_NW + wave) * 64 + lane] = acc[t];
     __syncthreads();
     if (wave == 0) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            f32x4 s = s_red[(t * 4 + 0) * 64 + lane];
-            s += s_red[(t * 4 + 1) * 64 + lane];
-            s += s_red[(t * 4 + 2) * 64 + lane];
-            s += s_red[(t * 4 + 3) * 64 + lane];
+            f32x4 s = s_red[(t * SMALL_NW) * 64 + lane];
+#pragma unroll
+            for (int w = 1; w < SMALL_NW; ++w) s += s_red[(t * SMALL_NW + w) * 64 + lane];
             acc[t] = s;
         }
     }
@@ -214,66 +252,71 @@ __device__ inline uint2 pack_bf16x4(float a, float b, float c, float d) {
 // ---------------------------------------------------------------- phase: RMSNorm + q/k/v + RoPE + KV append
 // Item = (head, block of 16 dims of the first half): the tile of dims e0..e0+16 and its RoPE partner
 // tile of dims half+e0.. are computed together so the rotation happens in registers.
-__device__ inline void phase_qkv(const SmallArgs& a, int layer, int wg, int nwg, uint16_t* s_act, float* s_rinv, f32x4* s_red) {
+__device__ __forceinline__ void phase_qkv(const SmallArgs& a, int layer, int wg, int nwg, uint16_t* s_act, f32x4* s_red) {
     const TascLayerW& L = a.layers[layer];
     const int half = a.hd / 2, eb_per_head = half / 16;
     const int n_items = (a.H + 2 * a.Hkv) * eb_per_head;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     BF16* kv_layer = a.kv_pool + (size_t)layer * a.kv_layer_stride;
+    const int nks = a.D / 32;
     bool staged = false;
     for (int item = wg; item < n_items; item += nwg) {
         const int head = item / eb_per_head, e0 = (item % eb_per_head) * 16;
         const BF16* W = (const BF16*)L.wqkv;
         const BF16* wrow[2] = {W + (size_t)(head * a.hd + e0) * a.D, W + (size_t)(head * a.hd + half + e0) * a.D};
-        f32x4 acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-        for (int kc0 = 0; kc0 < a.D; kc0 += SMALL_KC) {
-            const int kw = min(SMALL_KC, a.D - kc0);
-            if (!staged || a.D > SMALL_KC) {
-                if (staged) __syncthreads();
-                stage_normed(a.x, L.g1, nullptr, a.M, a.D, a.eps, kc0, kw, s_act, s_rinv);
-                staged = true;
+        bf16x8 w[2][SMALL_WKS];
+        load_w<2>(wrow, a.D, 0, nks, w);
+        // epilogue operands that do not depend on the product
+        const int m = lane & 15, e = e0 + 4 * (lane >> 4);
+        bool active = false;
+        int pos = 0;
+        BF16* page = nullptr;
+        float4 cs = make_float4(1, 1, 1, 1), sn = make_float4(0, 0, 0, 0);
+        if (wave == 0 && m < a.M) {
+            const int b = m / a.nq, i = m % a.nq;
+            active = i < a.n_rows[b];
+            pos = a.pos0[b] + i;
+            const int tpos = pos < a.max_pos ? pos : a.max_pos - 1;
+            if (head < a.H + a.Hkv) {
+                cs = *reinterpret_cast<const float4*>(a.rope_cos + (size_t)tpos * half + e);
+                sn = *reinterpret_cast<const float4*>(a.rope_sin + (size_t)tpos * half + e);
             }
-            mfma_tiles<2, true>(wrow, a.D, kc0, kw, s_act, acc);
+            if (active && head >= a.H)
+                page = kv_layer + (size_t)a.block_tab[(size_t)b * a.max_blocks + pos / TASC_KV_BLOCK] * a.page_elems;
         }
+        if (!staged) {
+            stage_normed(a.x, L.g1, nullptr, a.M, a.D, a.eps, s_act);
+            staged = true;
+        }
+        f32x4 acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+        mma_w<2>(w, nks, s_act, acc);
         reduce_waves<2>(acc, s_red);
-        if (wave == 0) {
-            const int m = lane & 15, e = e0 + 4 * (lane >> 4);
-            if (m < a.M) {
-                const int b = m / a.nq, i = m % a.nq;
-                const bool active = i < a.n_rows[b];
-                const int pos = a.pos0[b] + i;
-                const int tpos = pos < a.max_pos ? pos : a.max_pos - 1;
-                float ra[4], rc[4];
+        if (wave == 0 && m < a.M) {
+            const float c4[4] = {cs.x, cs.y, cs.z, cs.w}, s4[4] = {sn.x, sn.y, sn.z, sn.w};
+            float ra[4], rc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                ra[u] = acc[0][u] * c4[u] - acc[1][u] * s4[u];
+                rc[u] = acc[1][u] * c4[u] + acc[0][u] * s4[u];
+            }
+            if (head < a.H) {
+                BF16* qo = a.q + (size_t)m * a.H * a.hd + head * a.hd;
+                *reinterpret_cast<uint2*>(qo + e) = pack_bf16x4(ra[0], ra[1], ra[2], ra[3]);
+                *reinterpret_cast<uint2*>(qo + half + e) = pack_bf16x4(rc[0], rc[1], rc[2], rc[3]);
+            } else if (active) {
+                const int slot = pos % TASC_KV_BLOCK;
                 if (head < a.H + a.Hkv) {
-                    const float4 cs = *reinterpret_cast<const float4*>(a.rope_cos + (size_t)tpos * half + e);
-                    const float4 sn = *reinterpret_cast<const float4*>(a.rope_sin + (size_t)tpos * half + e);
-                    const float c4[4] = {cs.x, cs.y, cs.z, cs.w}, s4[4] = {sn.x, sn.y, sn.z, sn.w};
+                    const int g = head - a.H;
+                    BF16* kp = page + (size_t)(g * TASC_KV_BLOCK + slot) * a.hd;
+                    *reinterpret_cast<uint2*>(kp + e) = pack_bf16x4(ra[0], ra[1], ra[2], ra[3]);
+                    *reinterpret_cast<uint2*>(kp + half + e) = pack_bf16x4(rc[0], rc[1], rc[2], rc[3]);
+                } else {
+                    const int g = head - a.H - a.Hkv;
+                    BF16* vt = page + (size_t)a.Hkv * TASC_KV_BLOCK * a.hd + (size_t)g * a.hd * TASC_KV_BLOCK;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        ra[u] = acc[0][u] * c4[u] - acc[1][u] * s4[u];
-                        rc[u] = acc[1][u] * c4[u] + acc[0][u] * s4[u];
-                    }
-                }
-                if (head < a.H) {
-                    BF16* qo = a.q + (size_t)m * a.H * a.hd + head * a.hd;
-                    *reinterpret_cast<uint2*>(qo + e) = pack_bf16x4(ra[0], ra[1], ra[2], ra[3]);
-                    *reinterpret_cast<uint2*>(qo + half + e) = pack_bf16x4(rc[0], rc[1], rc[2], rc[3]);
-                } else if (active) {
-                    BF16* page = kv_layer + (size_t)a.block_tab[(size_t)b * a.max_blocks + pos / TASC_KV_BLOCK] * a.page_elems;
-                    const int slot = pos % TASC_KV_BLOCK;
-                    if (head < a.H + a.Hkv) {
-                        const int g = head - a.H;
-                        BF16* kp = page + (size_t)(g * TASC_KV_BLOCK + slot) * a.hd;
-                        *reinterpret_cast<uint2*>(kp + e) = pack_bf16x4(ra[0], ra[1], ra[2], ra[3]);
-                        *reinterpret_cast<uint2*>(kp + half + e) = pack_bf16x4(rc[0], rc[1], rc[2], rc[3]);
-                    } else {
-                        const int g = head - a.H - a.Hkv;
-                        BF16* vt = page + (size_t)a.Hkv * TASC_KV_BLOCK * a.hd + (size_t)g * a.hd * TASC_KV_BLOCK;
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            vt[(size_t)(e + u) * TASC_KV_BLOCK + slot] = BF16{f2bf(acc[0][u])};
-                            vt[(size_t)(half + e + u) * TASC_KV_BLOCK + slot] = BF16{f2bf(acc[1][u])};
-                        }
+                        vt[(size_t)(e + u) * TASC_KV_BLOCK + slot] = BF16{f2bf(acc[0][u])};
+                        vt[(size_t)(half + e + u) * TASC_KV_BLOCK + slot] = BF16{f2bf(acc[1][u])};
                     }
                 }
             }
@@ -283,7 +326,7 @@ __device__ inline void phase_qkv(const SmallArgs& a, int layer, int wg, int nwg,
 
 // ---------------------------------------------------------------- phases: projections with residual / SwiGLU
 // x[m][n] += sum_k src[m][k] W[n][k]    (output projection, down projection); item = 16 output features
-__device__ inline void phase_proj_resid(const SmallArgs& a, const BF16* __restrict__ W, const BF16* __restrict__ src, int N, int K,
+__device__ __forceinline__ void phase_proj_resid(const SmallArgs& a, const BF16* __restrict__ W, const BF16* __restrict__ src, int N, int K,
                                         int wg, int nwg, uint16_t* s_act, f32x4* s_red) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     bool staged = false;
@@ -291,45 +334,45 @@ __device__ inline void phase_proj_resid(const SmallArgs& a, const BF16* __restri
         const BF16* wrow[1] = {W + (size_t)item * 16 * K};
         f32x4 acc[1] = {{0, 0, 0, 0}};
         for (int kc0 = 0; kc0 < K; kc0 += SMALL_KC) {
-            const int kw = min(SMALL_KC, K - kc0);
+            const int kw = min(SMALL_KC, K - kc0), nks = kw / 32;
+            bf16x8 w[1][SMALL_WKS];
+            load_w<1>(wrow, K, kc0, nks, w);
             if (!staged || K > SMALL_KC) {
                 if (staged) __syncthreads();
                 stage_copy(src, a.M, K, kc0, kw, s_act);
                 staged = true;
             }
-            mfma_tiles<1, true>(wrow, K, kc0, kw, s_act, acc);
+            mma_w<1>(w, nks, s_act, acc);
         }
+        const int m = lane & 15, n = item * 16 + 4 * (lane >> 4);
+        float4 xv = make_float4(0, 0, 0, 0);
+        float4* xp = reinterpret_cast<float4*>(a.x + (size_t)m * N + n);
+        if (wave == 0 && m < a.M) xv = *xp;
         reduce_waves<1>(acc, s_red);
-        if (wave == 0) {
-            const int m = lane & 15, n = item * 16 + 4 * (lane >> 4);
-            if (m < a.M) {
-                float4* xp = reinterpret_cast<float4*>(a.x + (size_t)m * N + n);
-                float4 v = *xp;
-                v.x += acc[0][0]; v.y += acc[0][1]; v.z += acc[0][2]; v.w += acc[0][3];
-                *xp = v;
-            }
+        if (wave == 0 && m < a.M) {
+            xv.x += acc[0][0]; xv.y += acc[0][1]; xv.z += acc[0][2]; xv.w += acc[0][3];
+            *xp = xv;
         }
     }
 }
 
 // act[m][f] = silu(h W_gate[f]) * (h W_up[f]); item = 16 features (gate rows then up rows, interleaved per 16)
-__device__ inline void phase_gate_up(const SmallArgs& a, int layer, int wg, int nwg, uint16_t* s_act, float* s_rinv, f32x4* s_red) {
+__device__ __forceinline__ void phase_gate_up(const SmallArgs& a, int layer, int wg, int nwg, uint16_t* s_act, f32x4* s_red) {
     const TascLayerW& L = a.layers[layer];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nks = a.D / 32;
     bool staged = false;
     for (int item = wg; item < a.F / 16; item += nwg) {
         const BF16* W = (const BF16*)L.wgu + (size_t)item * 32 * a.D;
         const BF16* wrow[2] = {W, W + (size_t)16 * a.D};
-        f32x4 acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-        for (int kc0 = 0; kc0 < a.D; kc0 += SMALL_KC) {
-            const int kw = min(SMALL_KC, a.D - kc0);
-            if (!staged || a.D > SMALL_KC) {
-                if (staged) __syncthreads();
-                stage_normed(a.x, L.g2, nullptr, a.M, a.D, a.eps, kc0, kw, s_act, s_rinv);
-                staged = true;
-            }
-            mfma_tiles<2, true>(wrow, a.D, kc0, kw, s_act, acc);
+        bf16x8 w[2][SMALL_WKS];
+        load_w<2>(wrow, a.D, 0, nks, w);
+        if (!staged) {
+            stage_normed(a.x, L.g2, nullptr, a.M, a.D, a.eps, s_act);
+            staged = true;
         }
+        f32x4 acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+        mma_w<2>(w, nks, s_act, acc);
         reduce_waves<2>(acc, s_red);
         if (wave == 0) {
             const int m = lane & 15, f = item * 16 + 4 * (lane >> 4);
@@ -345,22 +388,23 @@ __device__ inline void phase_gate_up(const SmallArgs& a, int layer, int wg, int 
 
 // ---------------------------------------------------------------- phase: attention
 // Item = (sequence b, KV head g).  Query rows of the item: r = i * Gq + jq (i-th row of the sequence,
-// jq-th head of the group), processed in passes of at most 64 rows (32 when head_dim > 64).  Keys are
-// visited in tiles of 32 at absolute positions; tile t belongs to wave t mod 4.  S^T = K Q^T and
-// O^T = V^T P^T are both MFMA products whose lane layouts chain without a transpose: after S^T a lane
-// holds, for query row r = lane mod 16, the scores of keys {4q..4q+3} of each 16-key page (q = lane / 16),
-// which is exactly the B-operand slot of the second product when its A operand (V^T) is loaded with the
-// same key permutation.
+// jq-th head of the group), processed in passes of 32 rows (16 when head_dim = 128).  Keys are visited
+// in tiles of 32 at absolute positions; tile t belongs to wave t mod 8.  S^T = K Q^T and O^T = V^T P^T
+// are both MFMA products whose lane layouts chain without a transpose: after S^T a lane holds, for query
+// row r = lane mod 16, the scores of keys {4q..4q+3} of each 16-key page (q = lane / 16), which is
+// exactly the B-operand slot of the second product when its A operand (V^T) is loaded with the same key
+// permutation.  The waves' partial (max, sum, O) are merged pairwise in a fixed tree.
 template <int NKS>
-__device__ inline void phase_attn(const SmallArgs& a, int layer, int wg, int nwg, float* s_buf) {
+__device__ __forceinline__ void phase_attn(const SmallArgs& a, int layer, int wg, int nwg, float* s_buf) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    constexpr int hd = 32 * NKS, ndt = 2 * NKS, nks = NKS;
-    constexpr int rows_pass = hd > 64 ? 32 : 64, RT = rows_pass / 16;
+    constexpr int hd = 32 * NKS, ndt = 2 * NKS;
+    constexpr int RT = NKS <= 2 ? 2 : 1, rows_pass = 16 * RT;
     const int Gq = a.H / a.Hkv;
     const int R = a.nq * Gq;
     const BF16* kv_layer = a.kv_pool + (size_t)layer * a.kv_layer_stride;
     const size_t v_off = (size_t)a.Hkv * TASC_KV_BLOCK * hd;
     const int m = lane & 15, qd = lane >> 4;
+    float* slot_ml = s_buf + 4 * SMALL_ATT_SLOT;       // [4 slots][rows_pass][2]
     for (int item = wg; item < a.B * a.Hkv; item += nwg) {
         const int b = item / a.Hkv, g = item % a.Hkv;
         const int nr = a.n_rows[b], p0 = a.pos0[b];
@@ -373,24 +417,20 @@ __device__ inline void phase_attn(const SmallArgs& a, int layer, int wg, int nwg
             int qi[RT];
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
-                if (rt < RT) {
-                    const int r = r0 + 16 * rt + m;
-                    const int i = r / Gq, jq = r % Gq;
-                    const bool ok = r < R && i < nr;
-                    qi[rt] = ok ? p0 + i : -1;         // position of the query row, -1 = no such row
-                    const BF16* qp = a.q + (size_t)(b * a.nq + (ok ? i : 0)) * a.H * hd + (size_t)(g * Gq + (ok ? jq : 0)) * hd;
+                const int r = r0 + 16 * rt + m;
+                const int i = r / Gq, jq = r % Gq;
+                const bool ok = r < R && i < nr;
+                qi[rt] = ok ? p0 + i : -1;             // position of the query row, -1 = no such row
+                const BF16* qp = a.q + (size_t)(b * a.nq + (ok ? i : 0)) * a.H * hd + (size_t)(g * Gq + (ok ? jq : 0)) * hd;
 #pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks) {
-                        if (ks < nks) {
-                            bf16x8 v = *reinterpret_cast<const bf16x8*>(qp + 32 * ks + 8 * qd);
-                            if (!ok) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-                            qf[rt][ks] = v;
-                        }
-                    }
+                for (int ks = 0; ks < NKS; ++ks) {
+                    bf16x8 v = *reinterpret_cast<const bf16x8*>(qp + 32 * ks + 8 * qd);
+                    if (!ok) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                    qf[rt][ks] = v;
                 }
             }
             float mx[RT], lsum[RT];
-            f32x4 o[RT][ndt];                          // O^T tiles [rt][dim tile]: lane holds dims 4qd..+4 of row m
+            f32x4 o[RT][ndt];                          // O^T tiles: lane holds dims 16 dt + 4 qd .. +4 of row m
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 mx[rt] = -INFINITY;
@@ -398,109 +438,105 @@ __device__ inline void phase_attn(const SmallArgs& a, int layer, int wg, int nwg
 #pragma unroll
                 for (int dt = 0; dt < ndt; ++dt) o[rt][dt] = f32x4{0, 0, 0, 0};
             }
-            for (int t = wave; t < n_tiles; t += 4) {
-                const int key0 = t * 32;
-                // the two pages of this tile (the second may lie beyond the sequence)
-                const BF16* pg0 = kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK] * a.page_elems;
-                const bool has1 = key0 + 16 < L;
-                const BF16* pg1 = has1 ? kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK + 1] * a.page_elems : pg0;
-                // S^T tiles: A = K rows (key = m within the page), B = Q
-                f32x4 s0[RT], s1[RT];
+            // Tiles are taken TG at a time: all loads of the group are issued before its arithmetic, so a wave
+            // pays about one memory round trip per group instead of one per tile.
+            constexpr int TG = NKS <= 2 ? 3 : 1;
+            for (int tg = wave; tg < n_tiles; tg += SMALL_NW * TG) {
+                bf16x8 kf0[TG][NKS], kf1[TG][NKS];
+                bf16x8 vf[TG][ndt];
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt) { s0[rt] = f32x4{0, 0, 0, 0}; s1[rt] = f32x4{0, 0, 0, 0}; }
+                for (int j = 0; j < TG; ++j) {
+                    const int t = tg + j * SMALL_NW;
+                    if (t < n_tiles) {
+                        const int key0 = t * 32;
+                        // the two pages of this tile (the second may lie beyond the sequence)
+                        const BF16* pg0 = kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK] * a.page_elems;
+                        const bool has1 = key0 + 16 < L;
+                        const BF16* pg1 = has1 ? kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK + 1] * a.page_elems : pg0;
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    if (ks < nks) {
-                        const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(pg0 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
-                        const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(pg1 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
+                        for (int ks = 0; ks < NKS; ++ks) {
+                            kf0[j][ks] = *reinterpret_cast<const bf16x8*>(pg0 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
+                            kf1[j][ks] = *reinterpret_cast<const bf16x8*>(pg1 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
+                        }
 #pragma unroll
-                        for (int rt = 0; rt < RT; ++rt) {
-                            if (rt < RT) {
-                                s0[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[rt][ks], s0[rt], 0, 0, 0);
-                                s1[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[rt][ks], s1[rt], 0, 0, 0);
-                            }
+                        for (int dt = 0; dt < ndt; ++dt) {
+                            const uint2 h0 = *reinterpret_cast<const uint2*>(pg0 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd);
+                            const uint2 h1 = has1 ? *reinterpret_cast<const uint2*>(pg1 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd)
+                                                  : make_uint2(0, 0);
+                            vf[j][dt] = as_bf16x8(h0.x, h0.y, h1.x, h1.y);
                         }
                     }
                 }
-                // online softmax per query row; the lane holds keys key0 + 4qd + u (u<4) and key0 + 16 + 4qd + u
-                bf16x8 pf[RT];
-                float corr[RT];
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt) {
-                    if (rt < RT) {
-                        float sv[8];
-                        float tmax = -INFINITY;
+                for (int j = 0; j < TG; ++j) {
+                    const int t = tg + j * SMALL_NW;
+                    if (t < n_tiles) {
+                        const int key0 = t * 32;
+                        // S^T tiles: A = K rows (key = m within the page), B = Q
+                        f32x4 s0[RT], s1[RT];
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int key = key0 + (u < 4 ? 4 * qd + u : 16 + 4 * qd + (u - 4));
-                            const float s = (u < 4 ? s0[rt][u] : s1[rt][u - 4]) * a.scale;
-                            sv[u] = (key <= qi[rt]) ? s : -INFINITY;     // causal; also hides keys beyond the sequence
-                            tmax = fmaxf(tmax, sv[u]);
+                        for (int rt = 0; rt < RT; ++rt) { s0[rt] = f32x4{0, 0, 0, 0}; s1[rt] = f32x4{0, 0, 0, 0}; }
+#pragma unroll
+                        for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+                            for (int rt = 0; rt < RT; ++rt) {
+                                s0[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf0[j][ks], qf[rt][ks], s0[rt], 0, 0, 0);
+                                s1[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf1[j][ks], qf[rt][ks], s1[rt], 0, 0, 0);
+                            }
                         }
-                        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-                        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-                        const float m_new = fmaxf(mx[rt], tmax);
-                        float psum = 0.f;
-                        union { bf16x8 v; uint16_t u16[8]; } pk;
-                        if (m_new == -INFINITY) {
-                            corr[rt] = 1.f;
+                        // online softmax per query row; the lane holds keys key0 + 4qd + u (u<4) and key0 + 16 + 4qd + u
 #pragma unroll
-                            for (int u = 0; u < 8; ++u) pk.u16[u] = 0;
-                        } else {
-                            corr[rt] = __expf(mx[rt] - m_new);
+                        for (int rt = 0; rt < RT; ++rt) {
+                            float sv[8];
+                            float tmax = -INFINITY;
 #pragma unroll
                             for (int u = 0; u < 8; ++u) {
-                                const float p = __expf(sv[u] - m_new);
-                                const uint16_t pb = f2bf(p);
-                                pk.u16[u] = pb;
-                                psum += bf2f(pb);                        // the sum uses the rounded weights the product uses
+                                const int key = key0 + (u < 4 ? 4 * qd + u : 16 + 4 * qd + (u - 4));
+                                const float sc = (u < 4 ? s0[rt][u] : s1[rt][u - 4]) * a.scale;
+                                sv[u] = (key <= qi[rt]) ? sc : -INFINITY;   // causal; also hides keys beyond the sequence
+                                tmax = fmaxf(tmax, sv[u]);
                             }
-                        }
-                        psum += __shfl_xor(psum, 16);
-                        psum += __shfl_xor(psum, 32);
-                        lsum[rt] = lsum[rt] * corr[rt] + psum;
-                        mx[rt] = m_new;
-                        pf[rt] = pk.v;
-                    }
-                }
-                // O^T += V^T P^T : A = V^T rows (dim = 16 dt + m), keys {4qd..+4} of page 0 and of page 1
+                            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+                            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                            const float m_new = fmaxf(mx[rt], tmax);
+                            float psum = 0.f, corr = 1.f;
+                            uint32_t pw[4] = {0, 0, 0, 0};
+                            if (m_new != -INFINITY) {
+                                corr = __expf(mx[rt] - m_new);
 #pragma unroll
-                for (int dt = 0; dt < ndt; ++dt) {
-                    if (dt < ndt) {
-                        const BF16* v0p = pg0 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd;
-                        const BF16* v1p = pg1 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd;
-                        union { bf16x8 v; uint2 h[2]; } vf;
-                        vf.h[0] = *reinterpret_cast<const uint2*>(v0p);
-                        vf.h[1] = has1 ? *reinterpret_cast<const uint2*>(v1p) : make_uint2(0, 0);
+                                for (int u = 0; u < 8; ++u) {
+                                    const uint32_t pb = f2bf(__expf(sv[u] - m_new));
+                                    pw[u >> 1] |= pb << (16 * (u & 1));
+                                    psum += bf2f(pb);                    // the sum uses the rounded weights the product uses
+                                }
+                            }
+                            const bf16x8 pk = as_bf16x8(pw[0], pw[1], pw[2], pw[3]);
+                            psum += __shfl_xor(psum, 16);
+                            psum += __shfl_xor(psum, 32);
+                            lsum[rt] = lsum[rt] * corr + psum;
+                            mx[rt] = m_new;
+                            // O^T += V^T P^T
 #pragma unroll
-                        for (int rt = 0; rt < RT; ++rt) {
-                            if (rt < RT) {
-                                o[rt][dt] *= corr[rt];
-                                o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);
+                            for (int dt = 0; dt < ndt; ++dt) {
+                                o[rt][dt] *= corr;
+                                o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j][dt], pk, o[rt][dt], 0, 0, 0);
                             }
                         }
                     }
                 }
             }
-            // combine the 4 waves: (w0 + w1) + (w2 + w3), through LDS; rows_pass * hd floats per slot
-            float* slot_o[2] = {s_buf, s_buf + rows_pass * hd};
-            float* slot_ml = s_buf + 2 * rows_pass * hd;      // [2][rows_pass][2]
-            for (int round = 0; round < 2; ++round) {
-                const bool writer = round == 0 ? (wave & 1) : (wave == 2);
-                const bool reader = round == 0 ? !(wave & 1) : (wave == 0);
-                const int sl = round == 0 ? (wave >> 1) : 0;
+            // merge the waves pairwise, ((0+1)+(2+3))+((4+5)+(6+7)): a fixed tree through four slots of LDS
+            auto merge_round = [&](bool writer, bool reader, int sl) {
+                float* so = s_buf + sl * SMALL_ATT_SLOT;
                 if (writer) {
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        if (rt < RT) {
 #pragma unroll
-                            for (int dt = 0; dt < ndt; ++dt)
-                                if (dt < ndt)
-                                    *reinterpret_cast<f32x4*>(slot_o[sl] + (size_t)(16 * rt + m) * hd + 16 * dt + 4 * qd) = o[rt][dt];
-                            if (qd == 0) {
-                                slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 0] = mx[rt];
-                                slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 1] = lsum[rt];
-                            }
+                        for (int dt = 0; dt < ndt; ++dt)
+                            *reinterpret_cast<f32x4*>(so + (size_t)(16 * rt + m) * hd + 16 * dt + 4 * qd) = o[rt][dt];
+                        if (qd == 0) {
+                            slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 0] = mx[rt];
+                            slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 1] = lsum[rt];
                         }
                     }
                 }
@@ -508,41 +544,36 @@ __device__ inline void phase_attn(const SmallArgs& a, int layer, int wg, int nwg
                 if (reader) {
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        if (rt < RT) {
-                            const float m2 = slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 0];
-                            const float l2 = slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 1];
-                            const float mn = fmaxf(mx[rt], m2);
-                            const float c1 = mn == -INFINITY ? 1.f : __expf(mx[rt] - mn);
-                            const float c2 = mn == -INFINITY ? 1.f : __expf(m2 - mn);
-                            lsum[rt] = lsum[rt] * c1 + l2 * c2;
-                            mx[rt] = mn;
+                        const float m2 = slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 0];
+                        const float l2 = slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 1];
+                        const float mn = fmaxf(mx[rt], m2);
+                        const float c1 = mn == -INFINITY ? 1.f : __expf(mx[rt] - mn);
+                        const float c2 = mn == -INFINITY ? 1.f : __expf(m2 - mn);
+                        lsum[rt] = lsum[rt] * c1 + l2 * c2;
+                        mx[rt] = mn;
 #pragma unroll
-                            for (int dt = 0; dt < ndt; ++dt) {
-                                if (dt < ndt) {
-                                    const f32x4 o2 = *reinterpret_cast<const f32x4*>(slot_o[sl] + (size_t)(16 * rt + m) * hd + 16 * dt + 4 * qd);
-                                    o[rt][dt] = o[rt][dt] * c1 + o2 * c2;
-                                }
-                            }
+                        for (int dt = 0; dt < ndt; ++dt) {
+                            const f32x4 o2 = *reinterpret_cast<const f32x4*>(so + (size_t)(16 * rt + m) * hd + 16 * dt + 4 * qd);
+                            o[rt][dt] = o[rt][dt] * c1 + o2 * c2;
                         }
                     }
                 }
                 __syncthreads();
-            }
+            };
+            for (int stride = 1; stride < SMALL_NW; stride <<= 1)
+                merge_round((wave & (2 * stride - 1)) == stride, (wave & (2 * stride - 1)) == 0, (wave / (2 * stride)) & 3);
             if (wave == 0) {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
-                    if (rt < RT) {
-                        const int r = r0 + 16 * rt + m;
-                        if (r < R) {
-                            const int i = r / Gq, jq = r % Gq;
-                            const float inv = lsum[rt] > 0.f ? 1.0f / lsum[rt] : 0.f;
-                            BF16* op = a.att + (size_t)(b * a.nq + i) * a.H * hd + (size_t)(g * Gq + jq) * hd;
+                    const int r = r0 + 16 * rt + m;
+                    if (r < R) {
+                        const int i = r / Gq, jq = r % Gq;
+                        const float inv = lsum[rt] > 0.f ? 1.0f / lsum[rt] : 0.f;
+                        BF16* op = a.att + (size_t)(b * a.nq + i) * a.H * hd + (size_t)(g * Gq + jq) * hd;
 #pragma unroll
-                            for (int dt = 0; dt < ndt; ++dt)
-                                if (dt < ndt)
-                                    *reinterpret_cast<uint2*>(op + 16 * dt + 4 * qd) =
-                                        pack_bf16x4(o[rt][dt][0] * inv, o[rt][dt][1] * inv, o[rt][dt][2] * inv, o[rt][dt][3] * inv);
-                        }
+                        for (int dt = 0; dt < ndt; ++dt)
+                            *reinterpret_cast<uint2*>(op + 16 * dt + 4 * qd) =
+                                pack_bf16x4(o[rt][dt][0] * inv, o[rt][dt][1] * inv, o[rt][dt][2] * inv, o[rt][dt][3] * inv);
                     }
                 }
             }
@@ -551,61 +582,73 @@ __device__ inline void phase_attn(const SmallArgs& a, int layer, int wg, int nwg
 }
 
 // ---------------------------------------------------------------- phase: final norm + LM head + bias + strip argmax
-// Item = strip of TASC_LM_STRIP = 128 vocabulary rows = 8 tiles, two per wave (no k-split).
-__device__ inline void phase_lmhead(const SmallArgs& a, int wg, int nwg, uint16_t* s_act, float* s_rinv, float* s_best) {
+// Item = one strip of TASC_LM_STRIP = 128 vocabulary rows: 8 tiles, one per wave, each over the whole k.
+__device__ __forceinline__ void phase_lmhead(const SmallArgs& a, int wg, int nwg, uint16_t* s_act, float* s_best) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, qd = lane >> 4;
-    int32_t* s_besti = reinterpret_cast<int32_t*>(s_best + 4 * SMALL_ROWS);
+    int32_t* s_besti = reinterpret_cast<int32_t*>(s_best + SMALL_NW * SMALL_ROWS);
+    const int nks = a.D / 32;
+    const size_t woff = (size_t)m * a.D + 8 * qd;
+    const int aoff = m * SMALL_KP + 8 * qd;
     bool staged = false;
     for (int strip = wg; strip < a.n_strips; strip += nwg) {
+        const int v0 = strip * TASC_LM_STRIP + wave * 16;
+        const bool live = v0 < a.V;
+        int vr = v0;                                              // a ragged last tile reads the last 16 valid rows
+        if (vr + 16 > a.V) vr = a.V - 16;
+        const BF16* wrow = a.lm_head + (size_t)(live ? vr : 0) * a.D;
+        // first group of weight fragments and the lane's bias cursor, before the activations are staged
+        constexpr int WG_KS = 18;
+        bf16x8 w[WG_KS];
+#pragma unroll
+        for (int u = 0; u < WG_KS; ++u)
+            if (u < nks) w[u] = *reinterpret_cast<const bf16x8*>(wrow + woff + u * 32);
+        const bool own = live && m < a.n_sel;
+        int64_t bp = 0, be = 0;
+        float base = 0.f;
+        if (own && a.bias.rowptr) {
+            const int u = a.sel_tok[m];
+            const int64_t r0 = a.bias.rowptr[u];
+            bp = r0 + a.bias_ptr[(size_t)m * (a.n_strips + 1) + strip];
+            be = r0 + a.bias_ptr[(size_t)m * (a.n_strips + 1) + strip + 1];
+            base = a.bias.base[u];
+        }
         if (!staged) {
-            stage_normed(a.x, a.gf, a.sel_rows, a.n_sel, a.D, a.eps, 0, a.D, s_act, s_rinv);
+            stage_normed(a.x, a.gf, a.sel_rows, a.n_sel, a.D, a.eps, s_act);
             staged = true;
+        }
+        f32x4 acc = {0, 0, 0, 0};
+        for (int ks0 = 0; ks0 < nks; ks0 += WG_KS) {
+#pragma unroll
+            for (int u = 0; u < WG_KS; ++u) {
+                if (ks0 + u < nks) {
+                    const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(s_act + aoff + (ks0 + u) * 32);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u], bfr, acc, 0, 0, 0);
+                }
+            }
+            if (ks0 + WG_KS < nks) {
+#pragma unroll
+                for (int u = 0; u < WG_KS; ++u)
+                    if (ks0 + WG_KS + u < nks) w[u] = *reinterpret_cast<const bf16x8*>(wrow + woff + (ks0 + WG_KS + u) * 32);
+            }
         }
         float best = -INFINITY;
         int32_t best_i = 0x7FFFFFFF;
-        // bias row of this lane's row: entries with column >= the lane's first column of the strip
-        int64_t bp = 0, be = 0;
-        float base = 0.f;
-        const bool own = m < a.n_sel;
-        if (own && a.bias.rowptr) {
-            const int u = a.sel_tok[m];
-            int64_t lo = a.bias.rowptr[u];
-            be = a.bias.rowptr[u + 1];
-            int64_t hi = be;
-            const int c_first = strip * TASC_LM_STRIP + wave * 32;
-            while (lo < hi) {
-                const int64_t mid = (lo + hi) >> 1;
-                if (a.bias.col[mid] < c_first) lo = mid + 1; else hi = mid;
-            }
-            bp = lo;
-            base = a.bias.base[u];
-        }
-        for (int tt = 0; tt < 2; ++tt) {
-            const int v0 = strip * TASC_LM_STRIP + wave * 32 + tt * 16;   // wave's tiles are adjacent: columns ascend
-            if (v0 >= a.V) break;
-            int vr = v0;                                                   // clamp so a ragged last tile reads valid rows
-            if (vr + 16 > a.V) vr = a.V - 16;
-            const BF16* wrow[1] = {a.lm_head + (size_t)vr * a.D};
-            f32x4 acc[1] = {{0, 0, 0, 0}};
-            mfma_tiles<1, false>(wrow, a.D, 0, a.D, s_act, acc);
-            if (own) {
-                // this lane: columns vr + 4qd + u; bias entries of other lanes' columns are skipped over
+        if (own) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = vr + 4 * qd + u;
-                    if (c < v0) continue;                                  // column already covered by the previous tile
-                    float z = acc[0][u];
-                    if (a.bias.rowptr) {
-                        while (bp < be && a.bias.col[bp] < c) ++bp;
-                        z += (bp < be && a.bias.col[bp] == c) ? a.bias.val[bp] : base;
-                    }
-                    if (a.logits_dbg) a.logits_dbg[(size_t)m * a.V + c] = z;
-                    if (z > best) { best = z; best_i = c; }
+            for (int u = 0; u < 4; ++u) {
+                const int c = vr + 4 * qd + u;
+                if (c < v0) continue;                              // column belongs to the previous tile
+                float z = acc[u];
+                if (a.bias.rowptr) {
+                    while (bp < be && a.bias.col[bp] < c) ++bp;
+                    z += (bp < be && a.bias.col[bp] == c) ? a.bias.val[bp] : base;
                 }
+                if (a.logits_dbg) a.logits_dbg[(size_t)m * a.V + c] = z;
+                if (z > best) { best = z; best_i = c; }
             }
         }
-        // best over the 4 lane groups of the row, then over the 4 waves
+        // best over the 4 lane groups of the row, then over the waves of the strip
         for (int off = 16; off < 64; off <<= 1) {
             const float ov = __shfl_xor(best, off);
             const int32_t oi = __shfl_xor(best_i, off);
@@ -614,24 +657,25 @@ __device__ inline void phase_lmhead(const SmallArgs& a, int wg, int nwg, uint16_
         if (qd == 0) { s_best[wave * SMALL_ROWS + m] = best; s_besti[wave * SMALL_ROWS + m] = best_i; }
         __syncthreads();
         if (threadIdx.x < SMALL_ROWS && threadIdx.x < a.n_sel) {
-            float bv = s_best[threadIdx.x];
-            int32_t bi = s_besti[threadIdx.x];
-            for (int w = 1; w < 4; ++w) {
-                const float ov = s_best[w * SMALL_ROWS + threadIdx.x];
-                const int32_t oi = s_besti[w * SMALL_ROWS + threadIdx.x];
+            const int row = threadIdx.x;
+            float bv = s_best[row];
+            int32_t bi = s_besti[row];
+            for (int w8 = 1; w8 < SMALL_NW; ++w8) {
+                const float ov = s_best[w8 * SMALL_ROWS + row];
+                const int32_t oi = s_besti[w8 * SMALL_ROWS + row];
                 if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
             }
-            a.part_val[(size_t)threadIdx.x * a.n_strips + strip] = bv;
-            a.part_idx[(size_t)threadIdx.x * a.n_strips + strip] = bi;
+            a.part_val[(size_t)row * a.n_strips + strip] = bv;
+            a.part_idx[(size_t)row * a.n_strips + strip] = bi;
         }
         __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------- phase: argmax over strips, accept, rollback
-__device__ inline void phase_accept(const SmallArgs& a, int32_t* s_amax) {
+__device__ __forceinline__ void phase_accept(const SmallArgs& a, int32_t* s_amax) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int r = wave; r < a.n_sel; r += 4) {
+    for (int r = wave; r < a.n_sel; r += SMALL_NW) {
         float bv = -INFINITY;
         int32_t bi = 0x7FFFFFFF;
         for (int s = lane; s < a.n_strips; s += 64) {
@@ -686,27 +730,89 @@ __device__ inline void phase_accept(const SmallArgs& a, int32_t* s_amax) {
 }
 
 // ---------------------------------------------------------------- the persistent step kernel
-union SmallLds {
-    uint16_t act[SMALL_ROWS * SMALL_KP];   // staged activation rows
-    float attn[2 * 64 * 64 + 2 * 64 * 2];  // attention combine slots (rows_pass * hd = 4096 floats each)
-};
-
-__global__ __launch_bounds__(SMALL_THREADS) void k_small_step(SmallArgs a, int phase_begin, int phase_end) {
-    __shared__ __attribute__((aligned(16))) SmallLds lds;
-    __shared__ __attribute__((aligned(16))) f32x4 s_red[2 * 4 * 64];
-    __shared__ float s_rinv[SMALL_ROWS];
-    __shared__ float s_best[8 * SMALL_ROWS];
-    __shared__ int32_t s_amax[SMALL_ROWS];
-    const int wg = blockIdx.x, nwg = gridDim.x;
-    const int n_phases = 3 + 5 * a.n_layers;
-    u32 bar = 0;
-    for (int ph = phase_begin; ph < phase_end && ph < n_phases; ++ph) {
-        if (ph > phase_begin) {
-            if (__hip_atomic_load(a.bar_error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-            grid_sync(a, bar++, nwg);
+// cursor table of the LM-head bias: for every LM-head row r and strip s, how many entries of bias row
+// sel_tok[r] have a column below the strip's first column (s = n_strips: all of them)
+__device__ inline void build_bias_ptr(const SmallArgs& a, int worker, int n_workers) {
+    if (!a.bias.rowptr || a.n_sel <= 0) return;
+    const int per_row = a.n_strips + 1;
+    for (int idx = worker * SMALL_THREADS + threadIdx.x; idx < a.n_sel * per_row; idx += n_workers * SMALL_THREADS) {
+        const int r = idx / per_row, st = idx % per_row;
+        const int u = a.sel_tok[r];
+        const int64_t r0 = a.bias.rowptr[u];
+        int64_t lo = r0, hi = a.bias.rowptr[u + 1];
+        const int c_first = st * TASC_LM_STRIP;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (a.bias.col[mid] < c_first) lo = mid + 1; else hi = mid;
         }
+        a.bias_ptr[idx] = (int32_t)(lo - r0);
+    }
+}
+
+template <int NKS>
+__global__ __launch_bounds__(SMALL_THREADS) void k_small_step(SmallArgs a_in, int phase_begin, int phase_end) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    uint16_t* s_act = reinterpret_cast<uint16_t*>(lds + SMALL_LDS_ACT);
+    f32x4* s_red = reinterpret_cast<f32x4*>(lds + SMALL_LDS_RED);
+    float* s_attn = reinterpret_cast<float*>(lds);     // attention merge slots alias the staging area
+    __shared__ float s_best[2 * SMALL_NW * SMALL_ROWS];
+    __shared__ int32_t s_amax[SMALL_ROWS];
+    // The phases read their arguments from LDS, and so the small tables every phase consults (layer
+    // pointers, row counts, positions, block table): after a grid barrier has invalidated the caches a
+    // read of global memory costs a full memory round trip, and these reads would sit in front of the
+    // weight and activation loads that depend on them.
+    __shared__ SmallArgs s_args;
+    __shared__ TascLayerW s_layers[48];
+    __shared__ int32_t s_nrows[SMALL_ROWS], s_pos0[SMALL_ROWS];
+    __shared__ int32_t s_bt[1024];
+    if (threadIdx.x == 0) s_args = a_in;
+    if (a_in.n_layers <= 48)
+        for (int i = threadIdx.x; i < a_in.n_layers * (int)(sizeof(TascLayerW) / 8); i += SMALL_THREADS)
+            reinterpret_cast<u64*>(s_layers)[i] = reinterpret_cast<const u64*>(a_in.layers)[i];
+    if (threadIdx.x < a_in.B) {
+        s_nrows[threadIdx.x] = a_in.n_rows[threadIdx.x];
+        s_pos0[threadIdx.x] = a_in.pos0[threadIdx.x];
+    }
+    if (a_in.B * a_in.max_blocks <= 1024)
+        for (int i = threadIdx.x; i < a_in.B * a_in.max_blocks; i += SMALL_THREADS) s_bt[i] = a_in.block_tab[i];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (a_in.n_layers <= 48) s_args.layers = s_layers;
+        s_args.n_rows = s_nrows;
+        s_args.pos0 = s_pos0;
+        if (a_in.B * a_in.max_blocks <= 1024) s_args.block_tab = s_bt;
+    }
+    __syncthreads();
+    const SmallArgs& a = s_args;
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    const int n_phases = 3 + 5 * a.n_layers, n_lg_phases = 1 + 5 * a.n_layers;
+    const bool member = (wg % a.lg_stride == 0) && (wg / a.lg_stride < a.lg_count);
+    const int lw = wg / a.lg_stride, lnw = a.lg_count;
+    if (phase_begin == 0) {
+        // every workgroup outside the layer group (all of them if there is none) shares the cursor table
+        const int outside = nwg - lnw;
+        if (outside > 0) {
+            if (!member) build_bias_ptr(a, wg - min(lnw, (wg + a.lg_stride - 1) / a.lg_stride), outside);   // rank among the outsiders
+        } else {
+            build_bias_ptr(a, wg, nwg);
+        }
+    }
+    u32 bar_a = 0, bar_b = 0;
+    for (int ph = phase_begin; ph < phase_end && ph < n_phases; ++ph) {
+        if (ph < n_lg_phases) {
+            if (!member) continue;
+            if (ph > phase_begin) {
+                if (__hip_atomic_load(a.bar_error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+                grid_sync(a.bar_counter, a.bar_base + (u64)(++bar_a) * lnw, a.bar_error, 0);
+            }
+        } else if (ph > phase_begin) {
+            if (__hip_atomic_load(a.bar_error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+            grid_sync(a.barb_counter, a.barb_base + (u64)(++bar_b) * nwg, a.bar_error, member ? 0 : 1);
+        }
+        const bool ts = a.phase_ts != nullptr && wg < a.phase_ts_wgs && threadIdx.x == 0;
+        if (ts) a.phase_ts[((size_t)wg * n_phases + ph) * 2] = wall_clock64();
         if (ph == 0) {
-            for (int r = wg; r < a.M; r += nwg) {
+            for (int r = lw; r < a.M; r += lnw) {
                 const BF16* e = a.embed + (size_t)a.row_tok[r] * a.D;
                 for (int k = threadIdx.x * 8; k < a.D; k += SMALL_THREADS * 8) {
                     float v[8];
@@ -716,22 +822,22 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_small_step(SmallArgs a, int p
                     *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
                 }
             }
-        } else if (ph <= 5 * a.n_layers) {
+        } else if (ph < n_lg_phases) {
             const int layer = (ph - 1) / 5, sub = (ph - 1) % 5;
             const TascLayerW& L = a.layers[layer];
-            if (sub == 0) phase_qkv(a, layer, wg, nwg, lds.act, s_rinv, s_red);
-            else if (sub == 1) {
-                if (a.hd == 32) phase_attn<1>(a, layer, wg, nwg, lds.attn);
-                else if (a.hd == 64) phase_attn<2>(a, layer, wg, nwg, lds.attn);
-                else phase_attn<4>(a, layer, wg, nwg, lds.attn);
-            }
-            else if (sub == 2) phase_proj_resid(a, (const BF16*)L.wo, a.att, a.D, a.H * a.hd, wg, nwg, lds.act, s_red);
-            else if (sub == 3) phase_gate_up(a, layer, wg, nwg, lds.act, s_rinv, s_red);
-            else phase_proj_resid(a, (const BF16*)L.wd, a.act, a.D, a.F, wg, nwg, lds.act, s_red);
-        } else if (ph == 5 * a.n_layers + 1) {
-            if (a.n_sel > 0) phase_lmhead(a, wg, nwg, lds.act, s_rinv, s_best);
+            if (sub == 0) phase_qkv(a, layer, lw, lnw, s_act, s_red);
+            else if (sub == 1) phase_attn<NKS>(a, layer, lw, lnw, s_attn);
+            else if (sub == 2) phase_proj_resid(a, (const BF16*)L.wo, a.att, a.D, a.H * a.hd, lw, lnw, s_act, s_red);
+            else if (sub == 3) phase_gate_up(a, layer, lw, lnw, s_act, s_red);
+            else phase_proj_resid(a, (const BF16*)L.wd, a.act, a.D, a.F, lw, lnw, s_act, s_red);
+        } else if (ph == n_lg_phases) {
+            if (a.n_sel > 0) phase_lmhead(a, wg, nwg, s_act, s_best);
         } else {
             if (a.n_sel > 0 && wg == 0) phase_accept(a, s_amax);
+        }
+        if (ts) {
+            __builtin_amdgcn_s_waitcnt(0);
+            a.phase_ts[((size_t)wg * n_phases + ph) * 2 + 1] = wall_clock64();
         }
     }
 }

@@ -160,6 +160,7 @@ struct TascSessDev {
     int32_t* amax;       // [M_max] argmax token of every LM-head row
     float* att_part;     // attention split partials
     int32_t* drafts;     // [B, TASC_MAX_K] used by tasc_generate
+    int32_t* bias_ptr;   // [M_max, n_strips + 1] LM-head bias cursors of the small-batch kernel
 };
 
 struct tasc_session {
@@ -172,12 +173,14 @@ struct tasc_session {
     size_t page_elems;        // elements per page (K and V)
     TascSessDev d;
     u64* host_counters;       // pinned
-    u64 bar_base;             // arrivals the grid-barrier counter (counters[24]) has seen so far
+    u64 bar_base;             // arrivals the layer-group barrier counter (counters[24]) has seen so far
+    u64 barb_base;            // same for the whole-grid barrier counter (counters[26])
 };
 
 // counters[] slots used beyond the statistics
 #define TASC_CTR_BAR 24       // grid-barrier arrival counter
 #define TASC_CTR_BAR_ERR 25   // grid-barrier time-out flag (low 32 bits)
+#define TASC_CTR_BARB 26      // whole-grid barrier arrival counter
 
 // the tail of a verify step, fused into the forward when the small-batch kernel runs it
 struct TascVerifyTail {
@@ -193,6 +196,8 @@ struct TascVerifyTail {
 struct TascConfig {
     int small_path;           // 0: generic kernels only, 1: fused kernel one phase per launch, 2: persistent
     int small_grid;           // workgroups of the persistent kernel (0 = one per compute unit)
+    int layer_wgs;            // workgroups of its layer group (0 = default)
+    int layer_stride;         // the group's workgroup-id stride (0 = default)
 };
 extern TascConfig g_tasc_config;
 
