@@ -254,8 +254,13 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
  *                        the layer phases run on the workgroups stride * j, j < wgs, of that grid
  *                        (0 = defaults); the LM head always uses the whole grid.  Results do not
  *                        depend on these.
- * ---------------------------------------------------------------------------------------- */
-enum { TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3 };
+ *   TASC_CFG_TILED_PATH  bf16 forwards of more than 16 rows: 1 (default) = LDS-tiled MFMA kernels,
+ *                        0 = the type-generic kernels.
+ */
+enum {
+    TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3,
+    TASC_CFG_TILED_PATH = 4
+};
 tasc_status tasc_config_set(int32_t key, int32_t value);
 
 /* ------------------------------------------------------------------------------------------

@@ -314,7 +314,7 @@ def tasc_profile_read():
     return {KERNEL_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}
 
 
-TASC_CFG_SMALL_PATH, TASC_CFG_SMALL_GRID, TASC_CFG_SMALL_LAYER_WGS, TASC_CFG_SMALL_LAYER_STRIDE = 0, 1, 2, 3
+TASC_CFG_SMALL_PATH, TASC_CFG_SMALL_GRID, TASC_CFG_SMALL_LAYER_WGS, TASC_CFG_SMALL_LAYER_STRIDE, TASC_CFG_TILED_PATH = 0, 1, 2, 3, 4
 
 
 def tasc_config_set(key: int, value: int):

@@ -9,8 +9,9 @@
 #include "tasc_internal.h"
 #include "kernels_generic.h"
 #include "kernels_small.h"
+#include "kernels_tiled.h"
 
-TascConfig g_tasc_config = {2, 0, 0, 0};
+TascConfig g_tasc_config = {2, 0, 0, 0, 1};
 static u64* g_phase_ts = nullptr;
 static int64_t g_phase_ts_cap = 0;
 
@@ -28,6 +29,9 @@ extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
     } else if (key == TASC_CFG_SMALL_GRID) {
         TASC_REQUIRE(value >= 0 && value <= 4096, "config_set: grid %d outside [0, 4096]", value);
         g_tasc_config.small_grid = value;
+    } else if (key == TASC_CFG_TILED_PATH) {
+        TASC_REQUIRE(value == 0 || value == 1, "config_set: tiled path %d outside [0, 1]", value);
+        g_tasc_config.tiled_path = value;
     } else if (key == TASC_CFG_SMALL_LAYER_WGS) {
         TASC_REQUIRE(value >= 0 && value <= 4096, "config_set: layer workgroups %d outside [0, 4096]", value);
         g_tasc_config.layer_wgs = value;
@@ -113,6 +117,110 @@ tasc_status forward_generic(const tasc_model* m, tasc_session* s, int nq, int n_
             k_lmhead_generic<T><<<dim3(s->n_strips), dim3(256), 0, st>>>((const T*)d.h, (const T*)m->lm_head, d.sel_tok, n_sel,
                                                                       c.vocab, D, bias, d.part_val, d.part_idx, s->n_strips,
                                                                       logits_dbg);
+        }
+        {
+            PROF(TASC_KC_ACCEPT);
+            k_argmax_reduce<<<dim3(n_sel), dim3(64), 0, st>>>(d.part_val, d.part_idx, s->n_strips, d.amax);
+        }
+        TASC_LAUNCH_CHECK();
+    }
+    return TASC_OK;
+}
+
+// the LDS-tiled MFMA kernels serve bf16 forwards of any row count with these shapes
+bool tiled_path_fits(const tasc_model_desc& c) {
+    return c.dtype == TASC_BF16 && c.d_model % 64 == 0 && (c.n_heads * c.head_dim) % 64 == 0 && c.d_ffn % 64 == 0 &&
+           (c.head_dim == 32 || c.head_dim == 64 || c.head_dim == 128);
+}
+
+bool g_tiled_ready = false;
+
+tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
+    const tasc_model_desc& c = m->desc;
+    const TascSessDev& d = s->d;
+    if (!g_tiled_ready) {
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_STORE>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_LMHEAD>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
+        g_tiled_ready = true;
+    }
+    const int M = s->batch * nq;
+    const int D = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim, F = c.d_ffn;
+    const int nqkv = (H + 2 * Hkv) * hd, nqo = H * hd;
+    KvGeom gm{H, Hkv, hd, nq, s->max_blocks, s->page_elems};
+    const int n_mt = (M + TG_BM - 1) / TG_BM;
+    auto tiles = [&](int N) { return dim3((unsigned)(n_mt * ((N + TG_BN - 1) / TG_BN))); };
+    LmEpi none{};
+    const int rows_pass = hd > 64 ? 16 : 32;
+    const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
+    {
+        PROF(TASC_KC_PREPARE);
+        k_embed<BF16><<<dim3(M), dim3(64), 0, st>>>((const BF16*)m->embed, d.row_tok, D, d.x);
+    }
+    TASC_LAUNCH_CHECK();
+    for (int l = 0; l < c.n_layers; ++l) {
+        const TascLayerW& w = m->layers[l];
+        BF16* kv_layer = (BF16*)s->kv_pool + (size_t)l * s->kv_layer_stride;
+        {
+            PROF(TASC_KC_NORM);
+            k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (BF16*)d.h);
+        }
+        {
+            PROF(TASC_KC_GEMM_QKV);
+            k_gemm_tiled<TEPI_STORE><<<tiles(nqkv), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.h, (const BF16*)w.wqkv, M, nqkv, D,
+                                                                               d.qkv, nullptr, none);
+        }
+        {
+            PROF(TASC_KC_ROPE_KV);
+            k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(d.qkv, m->rope_cos, m->rope_sin, c.max_pos, d.n_rows, d.pos0, d.block_tab,
+                                                         gm, (BF16*)d.q, kv_layer);
+        }
+        {
+            PROF(TASC_KC_ATTN);
+            AttnArgs aa{(const BF16*)d.q, (BF16*)d.att, kv_layer, d.n_rows, d.pos0, d.block_tab, s->batch, nq, H, Hkv,
+                        s->max_blocks, s->page_elems, 1.0f / sqrtf((float)hd)};
+            if (hd == 32) k_attn_tiled<1><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+            else if (hd == 64) k_attn_tiled<2><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+            else k_attn_tiled<4><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+        }
+        {
+            PROF(TASC_KC_GEMM_O);
+            k_gemm_tiled<TEPI_RESID><<<tiles(D), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.att, (const BF16*)w.wo, M, D, nqo, d.x,
+                                                                            nullptr, none);
+        }
+        {
+            PROF(TASC_KC_NORM);
+            k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (BF16*)d.h);
+        }
+        {
+            PROF(TASC_KC_GEMM_GU);
+            k_gemm_tiled<TEPI_SWIGLU><<<tiles(2 * F), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.h, (const BF16*)w.wgu, M, 2 * F, D,
+                                                                                 nullptr, (BF16*)d.act, none);
+        }
+        {
+            PROF(TASC_KC_GEMM_D);
+            k_gemm_tiled<TEPI_RESID><<<tiles(D), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.act, (const BF16*)w.wd, M, D, F, d.x,
+                                                                            nullptr, none);
+        }
+        TASC_LAUNCH_CHECK();
+    }
+    if (n_sel > 0) {
+        {
+            PROF(TASC_KC_NORM);
+            k_rmsnorm<BF16><<<dim3(n_sel), dim3(64), 0, st>>>(d.x, m->gf, d.sel_rows, D, c.rms_eps, (BF16*)d.h);
+        }
+        LmEpi lm{BiasCsr{m->bias_rowptr, m->bias_col, m->bias_val, m->bias_base}, d.sel_tok, d.bias_ptr, d.part_val, d.part_idx,
+                 logits_dbg, s->n_strips};
+        {
+            PROF(TASC_KC_LMHEAD);
+            if (m->bias_rowptr) {
+                const int n = n_sel * (s->n_strips + 1);
+                k_bias_ptr<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(lm.bias, d.sel_tok, n_sel, s->n_strips, d.bias_ptr);
+            }
+            const int mt = (n_sel + TG_BM - 1) / TG_BM;
+            k_gemm_tiled<TEPI_LMHEAD><<<dim3((unsigned)(mt * s->n_strips)), dim3(256), TG_LDS_BYTES, st>>>(
+                (const BF16*)d.h, (const BF16*)m->lm_head, n_sel, c.vocab, D, nullptr, nullptr, lm);
         }
         {
             PROF(TASC_KC_ACCEPT);
@@ -224,8 +332,11 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel, float* logits_dbg,
                               TascVerifyTail* tail, hipStream_t st) {
     if (tail) tail->done = false;
-    if (g_tasc_config.small_path != 0 && small_path_fits(m->desc, s->batch, nq))
+    // The kernel family is a property of the session (its largest forward, batch * max_rows), not of this
+    // call's row count, so that a greedy step and a speculative step of one session use the same kernels.
+    if (g_tasc_config.small_path != 0 && small_path_fits(m->desc, s->batch, s->max_rows))
         return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);
+    if (g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc)) return forward_tiled(m, s, nq, n_sel, logits_dbg, st);
     if (m->desc.dtype == TASC_F32) return forward_generic<float>(m, s, nq, n_sel, logits_dbg, st);
     return forward_generic<BF16>(m, s, nq, n_sel, logits_dbg, st);
 }

@@ -198,6 +198,7 @@ struct TascConfig {
     int small_grid;           // workgroups of the persistent kernel (0 = one per compute unit)
     int layer_wgs;            // workgroups of its layer group (0 = default)
     int layer_stride;         // the group's workgroup-id stride (0 = default)
+    int tiled_path;           // 1: LDS-tiled MFMA kernels for bf16 forwards of more than 16 rows, 0: generic kernels
 };
 extern TascConfig g_tasc_config;
 

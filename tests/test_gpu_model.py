@@ -236,3 +236,61 @@ def test_small_batch_fused_kernel(heads):
         T.tasc_config_set(T.TASC_CFG_SMALL_PATH, 2)
     assert (results[1][0] == results[2][0]).all() and (results[1][1] == results[2][1]).all()
     assert (results[1][2] == results[2][2]).all(), "persistent and per-phase launches must be bit-identical"
+
+
+@pytest.mark.parametrize("heads", [(4, 2, 64), (2, 1, 128), (6, 2, 32)])
+def test_tiled_mfma_kernels(heads):
+    """bf16 forwards of more than 16 rows run on the LDS-tiled MFMA GEMMs and the MFMA paged attention:
+    several row tiles, ragged last tiles, against the oracle and against the type-generic kernels."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    H, Hkv, hd = heads
+    cfg = W.get_config("cfg1").scaled(dtype="bf16", n_layers=2, d_model=256 if H * hd == 256 else 192, n_heads=H, n_kv_heads=Hkv,
+                                      head_dim=hd, d_ffn=448, vocab=1000, batch=20, prompt_len=40, gen_len=24, k=7,
+                                      n_docs=1500, n_max=4)
+    rig = Rig(cfg, max_rows=16)                    # prompt chunks: 20 x 16 = 320 rows, verify: 20 x 8 = 160 rows
+    lens = [40 - (b * 7) % 30 for b in range(cfg.batch)]
+    rng = np.random.default_rng(11)
+    prompts = [rng.integers(0, cfg.vocab, n).astype(np.int32) for n in lens]
+    rig.prompts = np.concatenate(prompts)
+    rig.prompt_off = np.cumsum([0] + lens).astype(np.int64)
+    ref_tables = ON.build_tables_flat(rig.corpus[0], rig.corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
+    om = OM.OracleModel(cfg, rig.weights)
+    check = [0, 7, 19]                             # sequences whose logits the oracle follows
+    outs = {}
+    try:
+        for tiled in (1, 0):
+            print(f"heads {heads} tiled {tiled}", flush=True)
+            T.tasc_config_set(T.TASC_CFG_TILED_PATH, tiled)
+            out, st, tr = rig.generate(trace_steps=cfg.gen_len)
+            g_out, g_st, _ = rig.generate(k=0)
+            assert (out == g_out).all(), f"tiled {tiled}: speculative output differs from greedy"
+            for b in range(cfg.batch):
+                _replay(cfg, ref_tables, prompts[b].tolist(), tr[:, b], cfg.k, cfg.lambda_q16, cfg.p_min_ctx, out[b])
+            T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+            caches = {}
+            for b in check:
+                c = om.new_cache(rig.max_len)
+                om.forward(prompts[b].tolist(), c, last_only=True)
+                c.length = lens[b]
+                caches[b] = c
+            logits = torch.zeros((cfg.batch, cfg.k + 1, cfg.vocab), dtype=torch.float32, device="cuda")
+            drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+            worst = 0.0
+            for s in range(3):
+                T.tasc_draft(rig.ng, rig.session, rig.params(), drafts)
+                before = {b: T.tasc_session_get_tokens(rig.session, b) for b in check}
+                T.tasc_verify_step(rig.model, rig.session, drafts, cfg.k, None, None, logits)
+                got = logits.cpu().numpy()
+                d = drafts.cpu().numpy()
+                for b in check:
+                    z = om.forward([int(before[b][-1])] + d[b].tolist(), caches[b])
+                    worst = max(worst, float(np.abs(got[b].astype(np.float64) - z).max()))
+                    after = T.tasc_session_get_tokens(rig.session, b)
+                    caches[b].length += len(after) - len(before[b])
+            print(f"tiled {tiled}: max |logit - oracle| = {worst:.3e}, steps {st.steps}", flush=True)
+            assert worst <= 5e-2
+            outs[tiled] = out
+    finally:
+        T.tasc_config_set(T.TASC_CFG_TILED_PATH, 1)
