@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--cpu-steps", type=int, default=24, help="draft+verify steps of the CPU oracle sample (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB plain copy kernel 4 times (reference for rocprofv3 byte counters)")
+    ap.add_argument("--max-rows", type=int, default=0, help="rows per sequence and forward (prompt chunk length); 0 = default")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} is not supported",
@@ -96,12 +99,20 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     T.lib()
+
+    def note(msg):                                  # progress on stderr: the one JSON line stays alone on stdout
+        print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
     cfg = W.get_config(args.config)
+    note(f"{cfg.name}: generating corpus")
     corpus = W.make_corpus(cfg)
+    note(f"corpus {corpus[0].shape[0]} tokens; generating weights")
     weights = W.make_model(cfg, corpus)
+    note("weights done")
     prompts, poff = W.make_prompts(cfg)
-    max_rows = max(cfg.k + 1, 16)
+    max_rows = args.max_rows or max(cfg.k + 1, 16 if cfg.batch == 1 else 64)
     max_len = cfg.prompt_len + cfg.gen_len + 2 * max_rows
+    small = cfg.batch * max_rows <= 16          # the session then runs on the persistent fused kernel
     model = T.tasc_model_create(cfg, weights, max_len)
     session = T.tasc_session_create(model, cfg.batch, max_len, max_rows)
     d_corpus = torch.from_numpy(corpus[0]).cuda()           # inputs resident in HBM before the timed region
@@ -117,9 +128,11 @@ def main():
         ng.close()
         return st, bs
 
+    note("model and session on the device; warm-up")
     for _ in range(args.warmup):
         step()
-    T.tasc_profile_enable(["layers"])
+    note("timed region")
+    T.tasc_profile_enable(["layers" if small else "verify"])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     stats = [step() for _ in range(args.steps)]
@@ -146,17 +159,34 @@ def main():
 
     # roofline of the dominant kernel: the verify step (weights + live KV streamed once per step)
     # (the event pairs also bracket the 32 prompt-chunk launches of the same kernel: identical weight traffic)
-    ver_ms, ver_n = prof.get("layers", (0.0, 0))
+    ver_ms, ver_n = prof.get("layers" if small else "verify", (0.0, 0))
     mean_len = cfg.prompt_len + cfg.gen_len / 2.0
     alg_bytes, parts = algorithmic_bytes_verify(cfg, mean_len)
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy kernel);
+    # a separate profiler run, so the figure comes from its committed summary and only for the workload it covers
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "cfg2_k_small_step_hbm_traffic.txt")
+    if small and cfg.name == "cfg2" and os.path.exists(tpath):
+        for ln in open(tpath):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                traffic = int(ln.split(":")[1])
     roofline = None
     if ver_n:
         avg_ms = ver_ms / ver_n
         achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": None, "kernel": "k_small_step (persistent fused forward: all layers + LM head + argmax + accept in one launch)",
+                    "traffic": traffic, "kernel": ("k_small_step (persistent fused forward: all layers + LM head + argmax + accept in one launch)" if small
+                               else "verify step (all kernels of one target forward + accept)"),
                     "avg_launch_ms": avg_ms, "launches": ver_n, "algorithmic_bytes": alg_bytes, "bytes_breakdown": parts}
 
+    note("timed region done")
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            T.tasc_calibration_copy(dst, src, stream)
+        torch.cuda.synchronize()
+        del src, dst
     cpu = None
     if args.cpu_steps > 0:
         cpu = cpu_baseline(cfg, corpus, weights, prompts, args.cpu_steps)

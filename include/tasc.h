@@ -296,6 +296,11 @@ tasc_status tasc_profile_read(double* total_ms, int64_t* launches);
  * device_buf[(w * phases + p) * 2 + {0, 1}].  device_buf: DEVICE uint64[capacity]; NULL turns it off. */
 tasc_status tasc_profile_phases(uint64_t* device_buf, int64_t capacity);
 
+/* A plain device-to-device copy kernel (reads `bytes`, writes `bytes`; DEVICE pointers, 16-byte aligned,
+ * bytes a multiple of 16): the known-size reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE
+ * counters of the other kernels are scaled. */
+tasc_status tasc_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

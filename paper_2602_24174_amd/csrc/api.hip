@@ -280,7 +280,7 @@ WsLayout ws_layout(const tasc_model_desc& c, int B, int max_len, int max_rows) {
         M * HD * es, M * HD * es,                                    // q att
         M * (size_t)c.d_ffn * es,                                    // act
         M * n_strips * 4, M * n_strips * 4, M * 4,                   // part_val part_idx amax
-        16,                                                          // att_part (reserved)
+        8 * M * std::max<size_t>(HD + 2 * KD, c.d_model) * 4,        // att_part: k-slice partial sums of the narrow GEMMs
         (size_t)B * TASC_MAX_K * 4,                                  // drafts
         M * (n_strips + 1) * 4,                                      // bias_ptr
     };

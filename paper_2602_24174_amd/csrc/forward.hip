@@ -143,6 +143,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
         TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
         TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_LMHEAD>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_PARTIAL>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
         g_tiled_ready = true;
     }
     const int M = s->batch * nq;
@@ -152,6 +153,29 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
     const int n_mt = (M + TG_BM - 1) / TG_BM;
     auto tiles = [&](int N) { return dim3((unsigned)(n_mt * ((N + TG_BN - 1) / TG_BN))); };
     LmEpi none{};
+    // narrow outputs (few column tiles) are computed in k-slices; the slice count depends on N and K only
+    auto slices = [&](int N, int K) {
+        const int n_nt = (N + TG_BN - 1) / TG_BN, nk = K / TG_BK;
+        if (n_nt >= 64) return 1;
+        int ks = nk < TG_MAX_SLICES ? nk : TG_MAX_SLICES;
+        return ks < 1 ? 1 : ks;
+    };
+    // out (+)= A W^T through k-slices and the ordered reduction
+    auto gemm_sliced = [&](const BF16* A, const void* Wm, int N, int K, float* out, bool resid) {
+        const int ks = slices(N, K);
+        if (ks == 1) {
+            if (resid) k_gemm_tiled<TEPI_RESID><<<tiles(N), dim3(256), TG_LDS_BYTES, st>>>(A, (const BF16*)Wm, M, N, K, out, nullptr, none);
+            else k_gemm_tiled<TEPI_STORE><<<tiles(N), dim3(256), TG_LDS_BYTES, st>>>(A, (const BF16*)Wm, M, N, K, out, nullptr, none);
+            return;
+        }
+        dim3 g = tiles(N);
+        g.y = ks;
+        k_gemm_tiled<TEPI_PARTIAL><<<g, dim3(256), TG_LDS_BYTES, st>>>(A, (const BF16*)Wm, M, N, K, d.att_part, nullptr, none);
+        const size_t mn = (size_t)M * N;
+        const unsigned blocks = (unsigned)((mn / 4 + 255) / 256);
+        if (resid) k_splitk_reduce<true><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
+        else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
+    };
     const int rows_pass = hd > 64 ? 16 : 32;
     const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
     {
@@ -168,8 +192,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         }
         {
             PROF(TASC_KC_GEMM_QKV);
-            k_gemm_tiled<TEPI_STORE><<<tiles(nqkv), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.h, (const BF16*)w.wqkv, M, nqkv, D,
-                                                                               d.qkv, nullptr, none);
+            gemm_sliced((const BF16*)d.h, w.wqkv, nqkv, D, d.qkv, false);
         }
         {
             PROF(TASC_KC_ROPE_KV);
@@ -186,8 +209,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         }
         {
             PROF(TASC_KC_GEMM_O);
-            k_gemm_tiled<TEPI_RESID><<<tiles(D), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.att, (const BF16*)w.wo, M, D, nqo, d.x,
-                                                                            nullptr, none);
+            gemm_sliced((const BF16*)d.att, w.wo, D, nqo, d.x, true);
         }
         {
             PROF(TASC_KC_NORM);
@@ -200,8 +222,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         }
         {
             PROF(TASC_KC_GEMM_D);
-            k_gemm_tiled<TEPI_RESID><<<tiles(D), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.act, (const BF16*)w.wd, M, D, F, d.x,
-                                                                            nullptr, none);
+            gemm_sliced((const BF16*)d.act, w.wd, D, F, d.x, true);
         }
         TASC_LAUNCH_CHECK();
     }

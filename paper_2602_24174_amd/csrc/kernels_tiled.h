@@ -19,8 +19,12 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 #define TG_BK 64
 #define TG_LD (TG_BK + 8)                                     // padded LDS row (elements)
 #define TG_LDS_BYTES (2 * (TG_BM + TG_BN) * TG_LD * 2)        // 73728
+#define TG_MAX_SLICES 8                                       // most k-slices of a narrow GEMM
 
-enum { TEPI_STORE = 0, TEPI_RESID = 1, TEPI_SWIGLU = 2, TEPI_LMHEAD = 3 };
+// TEPI_PARTIAL: blockIdx.y selects one of gridDim.y slices of k; the slice's sums go to outf[slice][M][N] and
+// k_splitk_reduce adds the slices in order (plain store or residual add).  Used where N is too narrow for
+// the tile count to fill the chip; the number of slices depends on N and K only.
+enum { TEPI_STORE = 0, TEPI_RESID = 1, TEPI_SWIGLU = 2, TEPI_LMHEAD = 3, TEPI_PARTIAL = 4 };
 
 struct LmEpi {            // TEPI_LMHEAD only
     BiasCsr bias;
@@ -78,11 +82,19 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int nk = K / TG_BK;
-    load_tiles(0);
-    store_tiles(0);
+    int kt_begin = 0, nk = K / TG_BK;
+    if (EPI == TEPI_PARTIAL) {
+        const int per = (nk + gridDim.y - 1) / gridDim.y;
+        kt_begin = blockIdx.y * per;
+        nk = min(nk, kt_begin + per);
+        outf += (size_t)blockIdx.y * M * N;
+    }
+    if (kt_begin < nk) {
+        load_tiles(kt_begin * TG_BK);
+        store_tiles(kt_begin & 1);
+    }
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = kt_begin; kt < nk; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nk) load_tiles((kt + 1) * TG_BK);
         const uint16_t* bw = sW + (size_t)(buf * TG_BN + wn * 64 + (lane & 31)) * TG_LD + 8 * (lane >> 5);
@@ -204,6 +216,24 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, 
             }
         }
     }
+}
+
+// out[i] (+)= part[0][i] + part[1][i] + ... in slice order; 4 elements per thread
+template <bool RESID>
+__global__ void k_splitk_reduce(const float* __restrict__ part, int n_slices, size_t mn, float* __restrict__ out) {
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= mn) return;
+    float4 s = *reinterpret_cast<const float4*>(part + i);
+    for (int k = 1; k < n_slices; ++k) {
+        const float4 v = *reinterpret_cast<const float4*>(part + (size_t)k * mn + i);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    float4* o = reinterpret_cast<float4*>(out + i);
+    if (RESID) {
+        const float4 old = *o;
+        s.x += old.x; s.y += old.y; s.z += old.z; s.w += old.w;
+    }
+    *o = s;
 }
 
 // cursor table of the LM-head bias (see LmEpi): one thread per (row, strip boundary)

@@ -56,3 +56,20 @@ extern "C" tasc_status tasc_profile_read(double* total_ms, int64_t* launches) {
     g_used.clear();
     return TASC_OK;
 }
+
+// Plain copy kernel of known size: the reference against which hardware byte counters are scaled.
+namespace {
+__global__ void k_calibration_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
+extern "C" tasc_status tasc_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    TASC_REQUIRE(dst && src && bytes % 16 == 0 && ((uintptr_t)dst & 15) == 0 && ((uintptr_t)src & 15) == 0,
+                 "calibration_copy: buffers must be 16-byte aligned and a multiple of 16 bytes long");
+    k_calibration_copy<<<dim3(4096), dim3(256), 0, (hipStream_t)stream>>>((const uint4*)src, (uint4*)dst, bytes / 16);
+    TASC_LAUNCH_CHECK();
+    return TASC_OK;
+}

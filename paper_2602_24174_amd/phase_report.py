@@ -1,0 +1,82 @@
+"""Per-phase timing report of the persistent small-batch step kernel (tasc_profile_phases).
+
+    python -m paper_2602_24174_amd.phase_report [--config cfg2] [--grid G] [--layer-wgs N] [--layer-stride S]
+
+Builds the named workload with a reduced corpus (2,000 outputs: the tables do not matter for the forward's
+timing), prefills, runs a few warm verify steps, then one verify step with the per-phase wall-clock stamps
+on, and prints per layer-phase medians: the longest workgroup's work, the span from the first begin to the
+last end, and the barrier gap to the next phase.
+"""
+import argparse
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--layer-wgs", type=int, default=0)
+    ap.add_argument("--layer-stride", type=int, default=0)
+    ap.add_argument("--max-rows", type=int, default=16)
+    args = ap.parse_args()
+    import torch
+    import workload as W
+    import paper_2602_24174_amd as T
+
+    cfg = W.get_config(args.config).scaled(n_docs=2000)
+    if cfg.batch * args.max_rows > 16:
+        sys.exit("the persistent kernel only serves sessions with batch * max_rows <= 16")
+    corpus = W.make_corpus(cfg)
+    weights = W.make_model(cfg, corpus)
+    prompts, poff = W.make_prompts(cfg)
+    max_len = cfg.prompt_len + cfg.gen_len + 2 * args.max_rows
+    model = T.tasc_model_create(cfg, weights, max_len)
+    ng = T.tasc_ngram_build(corpus[0], corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
+    sess = T.tasc_session_create(model, cfg.batch, max_len, args.max_rows)
+    T.tasc_config_set(T.TASC_CFG_SMALL_GRID, args.grid)
+    T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WGS, args.layer_wgs)
+    T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_STRIDE, args.layer_stride)
+    T.tasc_session_prefill(model, sess, prompts, poff, cfg.gen_len)
+    params = T.spec_params(cfg.k, cfg.lambda_q16, cfg.p_min_ctx, 1)
+    drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+    n_ph = 3 + 5 * cfg.n_layers
+    n_wg = args.grid or torch.cuda.get_device_properties(0).multi_processor_count
+    buf = torch.zeros(n_wg * n_ph * 2, dtype=torch.int64, device="cuda")
+    for _ in range(5):
+        T.tasc_draft(ng, sess, params, drafts)
+        T.tasc_verify_step(model, sess, drafts, cfg.k)
+    T.tasc_profile_phases(buf)
+    T.tasc_draft(ng, sess, params, drafts)
+    T.tasc_verify_step(model, sess, drafts, cfg.k)
+    torch.cuda.synchronize()
+    T.tasc_profile_phases(None)
+
+    ts = buf.cpu().numpy().reshape(n_wg, n_ph, 2).astype(np.float64) / 100.0      # microseconds (100 MHz clock)
+    stride, lg = args.layer_stride or 1, args.layer_wgs or 48
+    members = [w for w in range(n_wg) if w % stride == 0 and w // stride < lg]
+    lay = ts[members][:, :1 + 5 * cfg.n_layers]
+    begin, end = lay[:, :, 0], lay[:, :, 1]
+    work = (end - begin).max(axis=0)
+    span = end.max(axis=0) - begin.min(axis=0)
+    gap = np.append(begin.min(axis=0)[1:] - end.max(axis=0)[:-1], 0.0)
+    per = lambda v: np.round(np.median(v[1:].reshape(cfg.n_layers, 5), axis=0), 2)
+    t0 = begin.min()
+    print(f"{cfg.name}: grid {n_wg} workgroups, layer group {len(members)} (stride {stride}); k = {cfg.k}, cached length "
+          f"about {cfg.prompt_len + 6 * (cfg.k + 1)}")
+    print(f"whole step {ts[:, :, 1].max() - t0:.1f} us; embedding + layers {end.max() - t0:.1f} us; "
+          f"LM head {ts[:, -2, 1].max() - ts[:, -2, 0].min():.1f} us; accept {ts[0, -1, 1] - ts[0, -1, 0]:.1f} us")
+    print("per-layer medians over the layers (us)        qkv    attn   o-proj  gate/up  down")
+    print("  longest workgroup's work                 ", per(work))
+    print("  first begin .. last end                  ", per(span))
+    print("  barrier: last end -> next phase's begin  ", per(gap))
+
+
+if __name__ == "__main__":
+    main()
