@@ -110,9 +110,9 @@ def main():
     weights = W.make_model(cfg, corpus)
     note("weights done")
     prompts, poff = W.make_prompts(cfg)
-    max_rows = args.max_rows or max(cfg.k + 1, 16 if cfg.batch == 1 else 64)
+    max_rows = args.max_rows or max(cfg.k + 1, 512 if cfg.batch == 1 else 64)
     max_len = cfg.prompt_len + cfg.gen_len + 2 * max_rows
-    small = cfg.batch * max_rows <= 16          # the session then runs on the persistent fused kernel
+    small = cfg.batch * min(max_rows, 16) <= 16   # decode steps then run on the persistent fused kernel
     model = T.tasc_model_create(cfg, weights, max_len)
     session = T.tasc_session_create(model, cfg.batch, max_len, max_rows)
     d_corpus = torch.from_numpy(corpus[0]).cuda()           # inputs resident in HBM before the timed region

@@ -71,6 +71,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise TascError(TASC_EHIP, f"{LIB_PATH} is not built; run `python -m paper_2602_24174_amd.build`")
+        # PyTorch first: it supplies the device memory and streams, and the process must end up with ONE HIP
+        # runtime.  If libtasc.so pulled in the system's libamdhip64 before torch loaded its own, the runtime
+        # that initialises second finds no device.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.tasc_last_error.restype = C.c_char_p
         L.tasc_session_kv_bytes.restype = C.c_size_t

@@ -353,9 +353,11 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel, float* logits_dbg,
                               TascVerifyTail* tail, hipStream_t st) {
     if (tail) tail->done = false;
-    // The kernel family is a property of the session (its largest forward, batch * max_rows), not of this
-    // call's row count, so that a greedy step and a speculative step of one session use the same kernels.
-    if (g_tasc_config.small_path != 0 && small_path_fits(m->desc, s->batch, s->max_rows))
+    // The kernel family of a decode step (nq <= 16 rows per sequence) is a property of the session, not of the
+    // call's row count, so that a greedy step and a speculative step of one session use the same kernels and
+    // reduce every row in the same order.  Prompt chunks of more than 16 rows always take the tiled kernels.
+    const int decode_rows = s->max_rows < SMALL_ROWS ? s->max_rows : SMALL_ROWS;
+    if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m->desc, s->batch, decode_rows))
         return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);
     if (g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc)) return forward_tiled(m, s, nq, n_sel, logits_dbg, st);
     if (m->desc.dtype == TASC_F32) return forward_generic<float>(m, s, nq, n_sel, logits_dbg, st);

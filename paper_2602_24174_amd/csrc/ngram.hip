@@ -70,45 +70,90 @@ __device__ inline bool same_window(const int32_t* __restrict__ tok, u64 p, const
     return eq;
 }
 
-// One thread per corpus position; the window of N tokens starting there is counted if it lies
-// inside its document.  Consecutive lanes read consecutive positions (coalesced scan).
+// Counting in two levels.  A workgroup takes chunks of kChunk consecutive corpus positions (coalesced scan,
+// the chunk's tokens staged in LDS), counts the chunk's windows in an LDS hash table whose slots name their
+// key by a position inside the chunk, and then adds every distinct window of the chunk to the global table
+// once, with its chunk count.  Task corpora concentrate on few n-grams (the paper's typical-set argument), so
+// the frequent ones would otherwise serialise hundreds of thousands of atomics on one address.
+constexpr int kChunk = 2048;
+constexpr int kLdsSlots = 4096;
+
 template <int N>
-__global__ __launch_bounds__(kThreads) void k_count(const int32_t* __restrict__ tok,
-                                                    const uint8_t* __restrict__ rem, u64 T, int bits,
-                                                    u64* slots, u64 mask) {
-    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= T || rem[i] < N) return;
-    int32_t w[N];
-    u64 lo = 0, hi = 0;
+__global__ __launch_bounds__(kThreads) void k_count(const int32_t* __restrict__ tok, const uint8_t* __restrict__ rem, u64 T,
+                                                    int bits, u64* slots, u64 mask) {
+    __shared__ int32_t s_tok[kChunk + TASC_MAX_ORDER];
+    __shared__ u64 s_slot[kLdsSlots];
+    const int tid = threadIdx.x;
+    for (u64 base = (u64)blockIdx.x * kChunk; base < T; base += (u64)gridDim.x * kChunk) {
+        const int n_here = (int)min((u64)(kChunk + N - 1), T - base);
+        for (int i = tid; i < n_here; i += kThreads) s_tok[i] = tok[base + i];
+        for (int i = tid; i < kLdsSlots; i += kThreads) s_slot[i] = 0;
+        __syncthreads();
+        const int n_win = (int)min((u64)kChunk, T - base);
+        for (int i = tid; i < n_win; i += kThreads) {
+            if (rem[base + i] < N) continue;           // the window would leave its document
+            u64 lo = 0, hi = 0;
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-        w[j] = tok[i + j];
-        tasc_key_put(lo, hi, j, bits, (u32)w[j]);
-    }
-    u64 idx = tasc_hash_key(lo, hi, N) & mask;
-    for (u64 probe = 0; probe <= mask; ++probe) {
-        u64 s = __hip_atomic_load(&slots[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (s == 0) {
-            u64 old = atomicCAS(&slots[idx], 0ull, ((i + 1) << 32) | 1ull);
-            if (old == 0) return;
-            s = old;
+            for (int j = 0; j < N; ++j) tasc_key_put(lo, hi, j, bits, (u32)s_tok[i + j]);
+            u32 idx = (u32)(tasc_hash_key(lo, hi, N) >> 20) & (kLdsSlots - 1);
+            for (int probe = 0; probe < kLdsSlots; ++probe) {
+                u64 sl = s_slot[idx];
+                if (sl == 0) {
+                    const u64 old = atomicCAS(&s_slot[idx], 0ull, ((u64)(i + 1) << 32) | 1ull);
+                    if (old == 0) break;
+                    sl = old;
+                }
+                const int p = (int)(sl >> 32) - 1;
+                bool eq = true;
+#pragma unroll
+                for (int j = 0; j < N; ++j) eq = eq && (s_tok[p + j] == s_tok[i + j]);
+                if (eq) {
+                    atomicAdd(&s_slot[idx], 1ull);
+                    break;
+                }
+                idx = (idx + 1) & (kLdsSlots - 1);
+            }
         }
-        u64 p = (s >> 32) - 1;
-        if (same_window<N>(tok, p, w)) {
-            atomicAdd(&slots[idx], 1ull);
-            return;
+        __syncthreads();
+        for (int sidx = tid; sidx < kLdsSlots; sidx += kThreads) {
+            const u64 sl = s_slot[sidx];
+            if (sl == 0) continue;
+            const int p = (int)(sl >> 32) - 1;
+            const u64 cnt = sl & 0xFFFFFFFFull;
+            int32_t w[N];
+            u64 lo = 0, hi = 0;
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                w[j] = s_tok[p + j];
+                tasc_key_put(lo, hi, j, bits, (u32)w[j]);
+            }
+            u64 idx = tasc_hash_key(lo, hi, N) & mask;
+            for (u64 probe = 0; probe <= mask; ++probe) {
+                u64 g = __hip_atomic_load(&slots[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (g == 0) {
+                    const u64 old = atomicCAS(&slots[idx], 0ull, ((base + p + 1) << 32) | cnt);
+                    if (old == 0) break;
+                    g = old;
+                }
+                if (same_window<N>(tok, (g >> 32) - 1, w)) {
+                    atomicAdd(&slots[idx], cnt);
+                    break;
+                }
+                idx = (idx + 1) & mask;
+            }
         }
-        idx = (idx + 1) & mask;
+        __syncthreads();
     }
 }
 
 // counters[0] = distinct n-grams, counters[1] = kept n-grams
-__global__ void k_tally(const u64* slots, u64 cap, u32 p_min, u64* counters) {
+__global__ __launch_bounds__(kThreads) void k_tally(const u64* slots, u64 cap, u32 p_min, u64* counters) {
+    __shared__ u32 s_d[kThreads / 64], s_k[kThreads / 64];
     u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-    u64 stride = (u64)gridDim.x * blockDim.x;
+    const u64 stride = (u64)gridDim.x * blockDim.x;
     u32 distinct = 0, kept = 0;
     for (; i < cap; i += stride) {
-        u64 s = slots[i];
+        const u64 s = slots[i];
         distinct += s != 0;
         kept += (s != 0) && ((u32)s >= p_min);
     }
@@ -116,9 +161,13 @@ __global__ void k_tally(const u64* slots, u64 cap, u32 p_min, u64* counters) {
         distinct += __shfl_xor(distinct, o);
         kept += __shfl_xor(kept, o);
     }
-    if ((threadIdx.x & 63) == 0) {
-        if (distinct) atomicAdd(&counters[0], (u64)distinct);
-        if (kept) atomicAdd(&counters[1], (u64)kept);
+    if ((threadIdx.x & 63) == 0) { s_d[threadIdx.x >> 6] = distinct; s_k[threadIdx.x >> 6] = kept; }
+    __syncthreads();
+    if (threadIdx.x == 0) {      // one pair of atomics per workgroup, not per wave
+        u64 d = 0, k = 0;
+        for (int w = 0; w < kThreads / 64; ++w) { d += s_d[w]; k += s_k[w]; }
+        if (d) atomicAdd(&counters[0], d);
+        if (k) atomicAdd(&counters[1], k);
     }
 }
 
@@ -200,7 +249,8 @@ u64 pow2_at_least(u64 v) {
 
 template <int N>
 void launch_count(const int32_t* tok, const uint8_t* rem, u64 T, int bits, u64* slots, u64 mask, hipStream_t st) {
-    k_count<N><<<dim3((unsigned)((T + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(tok, rem, T, bits, slots, mask);
+    const u64 chunks = (T + kChunk - 1) / kChunk;
+    k_count<N><<<dim3((unsigned)std::min<u64>(chunks, 1u << 20)), dim3(kThreads), 0, st>>>(tok, rem, T, bits, slots, mask);
 }
 template <int N>
 void launch_keep(const int32_t* tok, const u64* slots, u64 cap, u32 p_min, int bits, TascSlot* full, u64 fm,
@@ -330,7 +380,7 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
         }
         TASC_LAUNCH_CHECK();
         TASC_HIP(hipEventRecord(evc1, st));
-        k_tally<<<dim3((unsigned)std::min<u64>((cap + kThreads - 1) / kThreads, 1u << 14)), dim3(kThreads), 0, st>>>(
+        k_tally<<<dim3((unsigned)std::min<u64>((cap + kThreads - 1) / kThreads, 2048)), dim3(kThreads), 0, st>>>(
             d_slots, cap, (u32)p_min, d_counters);
         TASC_LAUNCH_CHECK();
         TASC_HIP(hipMemcpyAsync(h_counters, d_counters, 3 * sizeof(u64), hipMemcpyDeviceToHost, st));

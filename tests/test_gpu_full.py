@@ -20,7 +20,7 @@ def _sampled_tables(tok, off, n, p_min, mod, rem):
     return w[keep], c[keep]
 
 
-@pytest.mark.parametrize("name,max_rows,n_steps,sample", [("cfg2", 16, 8, None), ("cfg3", 64, 2, (16, 3))])
+@pytest.mark.parametrize("name,max_rows,n_steps,sample", [("cfg2", 512, 8, None), ("cfg3", 64, 2, (16, 3))])
 def test_full_size_config(name, max_rows, n_steps, sample):
     import torch
     import paper_2602_24174_amd as T
