@@ -135,27 +135,54 @@ bool tiled_path_fits(const tasc_model_desc& c) {
 
 bool g_tiled_ready = false;
 
+// tile shapes: 128 x 128 on 4 waves, and 256 x 256 on 8 waves for row counts where the GEMMs are MFMA-bound.
+// Both reduce every output element over k in the same order, so the choice may depend on the row count.
+#define TILE_SMALL 128, 128, 2, 2
+#define TILE_LARGE 256, 256, 2, 4
+constexpr int kLargeTileRows = 384;
+
+template <int EPI>
+tasc_status tiled_attrs() {
+    TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_SMALL>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TG_LDS_BYTES(128, 128)));
+    TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TG_LDS_BYTES(256, 256)));
+    return TASC_OK;
+}
+
+// launches out = epilogue(A W^T) with the tile shape that suits M; `slices` > 1 only for TEPI_PARTIAL
+template <int EPI>
+void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf, BF16* outb, const LmEpi& lm, int slices,
+                 hipStream_t st) {
+    if (M >= kLargeTileRows) {
+        dim3 g((unsigned)(((M + 255) / 256) * ((N + 255) / 256)), (unsigned)slices);
+        k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+    } else {
+        dim3 g((unsigned)(((M + 127) / 128) * ((N + 127) / 128)), (unsigned)slices);
+        k_gemm_tiled<EPI, TILE_SMALL><<<g, dim3(256), TG_LDS_BYTES(128, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+    }
+}
+
 tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
     if (!g_tiled_ready) {
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_STORE>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_LMHEAD>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<TEPI_PARTIAL>), hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES));
+        tasc_status rc;
+        if ((rc = tiled_attrs<TEPI_STORE>()) != TASC_OK) return rc;
+        if ((rc = tiled_attrs<TEPI_RESID>()) != TASC_OK) return rc;
+        if ((rc = tiled_attrs<TEPI_SWIGLU>()) != TASC_OK) return rc;
+        if ((rc = tiled_attrs<TEPI_LMHEAD>()) != TASC_OK) return rc;
+        if ((rc = tiled_attrs<TEPI_PARTIAL>()) != TASC_OK) return rc;
         g_tiled_ready = true;
     }
     const int M = s->batch * nq;
     const int D = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim, F = c.d_ffn;
     const int nqkv = (H + 2 * Hkv) * hd, nqo = H * hd;
     KvGeom gm{H, Hkv, hd, nq, s->max_blocks, s->page_elems};
-    const int n_mt = (M + TG_BM - 1) / TG_BM;
-    auto tiles = [&](int N) { return dim3((unsigned)(n_mt * ((N + TG_BN - 1) / TG_BN))); };
     LmEpi none{};
     // narrow outputs (few column tiles) are computed in k-slices; the slice count depends on N and K only
     auto slices = [&](int N, int K) {
-        const int n_nt = (N + TG_BN - 1) / TG_BN, nk = K / TG_BK;
+        const int n_nt = (N + 127) / 128, nk = K / TG_BK;
         if (n_nt >= 64) return 1;
         int ks = nk < TG_MAX_SLICES ? nk : TG_MAX_SLICES;
         return ks < 1 ? 1 : ks;
@@ -164,13 +191,11 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
     auto gemm_sliced = [&](const BF16* A, const void* Wm, int N, int K, float* out, bool resid) {
         const int ks = slices(N, K);
         if (ks == 1) {
-            if (resid) k_gemm_tiled<TEPI_RESID><<<tiles(N), dim3(256), TG_LDS_BYTES, st>>>(A, (const BF16*)Wm, M, N, K, out, nullptr, none);
-            else k_gemm_tiled<TEPI_STORE><<<tiles(N), dim3(256), TG_LDS_BYTES, st>>>(A, (const BF16*)Wm, M, N, K, out, nullptr, none);
+            if (resid) launch_gemm<TEPI_RESID>(A, Wm, M, N, K, out, nullptr, none, 1, st);
+            else launch_gemm<TEPI_STORE>(A, Wm, M, N, K, out, nullptr, none, 1, st);
             return;
         }
-        dim3 g = tiles(N);
-        g.y = ks;
-        k_gemm_tiled<TEPI_PARTIAL><<<g, dim3(256), TG_LDS_BYTES, st>>>(A, (const BF16*)Wm, M, N, K, d.att_part, nullptr, none);
+        launch_gemm<TEPI_PARTIAL>(A, Wm, M, N, K, d.att_part, nullptr, none, ks, st);
         const size_t mn = (size_t)M * N;
         const unsigned blocks = (unsigned)((mn / 4 + 255) / 256);
         if (resid) k_splitk_reduce<true><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
@@ -217,8 +242,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         }
         {
             PROF(TASC_KC_GEMM_GU);
-            k_gemm_tiled<TEPI_SWIGLU><<<tiles(2 * F), dim3(256), TG_LDS_BYTES, st>>>((const BF16*)d.h, (const BF16*)w.wgu, M, 2 * F, D,
-                                                                                 nullptr, (BF16*)d.act, none);
+            launch_gemm<TEPI_SWIGLU>((const BF16*)d.h, w.wgu, M, 2 * F, D, nullptr, (BF16*)d.act, none, 1, st);
         }
         {
             PROF(TASC_KC_GEMM_D);
@@ -239,9 +263,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
                 const int n = n_sel * (s->n_strips + 1);
                 k_bias_ptr<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(lm.bias, d.sel_tok, n_sel, s->n_strips, d.bias_ptr);
             }
-            const int mt = (n_sel + TG_BM - 1) / TG_BM;
-            k_gemm_tiled<TEPI_LMHEAD><<<dim3((unsigned)(mt * s->n_strips)), dim3(256), TG_LDS_BYTES, st>>>(
-                (const BF16*)d.h, (const BF16*)m->lm_head, n_sel, c.vocab, D, nullptr, nullptr, lm);
+            launch_gemm<TEPI_LMHEAD>((const BF16*)d.h, m->lm_head, n_sel, c.vocab, D, nullptr, nullptr, lm, 1, st);
         }
         {
             PROF(TASC_KC_ACCEPT);

@@ -3,7 +3,7 @@
 // paged GQA attention kernel on the same MFMA scheme as the small-batch kernel.
 //
 // GEMM: out[M, N] = A[M, K] W[N, K]^T, both operands k-contiguous.  A workgroup of 4 waves computes a
-// 128 (n) x 128 (m) tile; each wave a 64 x 64 quadrant as 2 x 2 v_mfma_f32_32x32x16_bf16 tiles with the
+// BN (n) x BM (m) tile, 128 x 128 on 4 waves or 256 x 256 on 8; each wave a block of v_mfma_f32_32x32x16_bf16 tiles with the
 // WEIGHT rows as the A operand, so a lane ends up with runs of 4 consecutive output features of one row.
 // k advances in steps of 64 through double-buffered LDS tiles (global -> registers -> LDS while the MFMAs
 // of the previous step run).  A row's result depends only on its own data and the fixed k order, not on
@@ -14,11 +14,9 @@
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-#define TG_BM 128   // rows (m) per workgroup tile
-#define TG_BN 128   // output features (n) per workgroup tile
 #define TG_BK 64
 #define TG_LD (TG_BK + 8)                                     // padded LDS row (elements)
-#define TG_LDS_BYTES (2 * (TG_BM + TG_BN) * TG_LD * 2)        // 73728
+#define TG_LDS_BYTES(BN, BM) (2 * ((BN) + (BM)) * TG_LD * 2)   // 73728 for 128 x 128, 147456 for 256 x 256
 #define TG_MAX_SLICES 8                                       // most k-slices of a narrow GEMM
 
 // TEPI_PARTIAL: blockIdx.y selects one of gridDim.y slices of k; the slice's sums go to outf[slice][M][N] and
@@ -39,46 +37,80 @@ struct LmEpi {            // TEPI_LMHEAD only
 // rows of the accumulator a lane holds: element i of a 32x32 tile is output feature 8 (i / 4) + 4 (lane / 32) + i % 4
 __device__ inline int tile_row(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 
-template <int EPI>
-__global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, const BF16* __restrict__ W, int M, int N, int K,
-                                                    float* __restrict__ outf, BF16* __restrict__ outb, LmEpi lm) {
+// BN x BM = output features x rows of the workgroup tile; WN x WM waves, each computing a
+// (BN / WN) x (BM / WM) block as TI x TJ MFMA tiles of 32 x 32.
+template <int EPI, int BN, int BM, int WN, int WM>
+__global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_gemm_tiled(const BF16* __restrict__ A, const BF16* __restrict__ W, int M, int N,
+                                                             int K, float* __restrict__ outf, BF16* __restrict__ outb, LmEpi lm) {
+    constexpr int THREADS = 64 * WN * WM;
+    constexpr int SN = BN / WN, SM = BM / WM;          // the wave's span in n and m
+    constexpr int TI = SN / 32, TJ = SM / 32;
+    constexpr int ROWS_PASS = THREADS / 8;             // tile rows one staging pass covers (8 threads x 16 bytes per row)
+    constexpr int PW = BN / ROWS_PASS, PA = BM / ROWS_PASS;
+    static_assert(SN % 32 == 0 && SM % 32 == 0 && BN % ROWS_PASS == 0 && BM % ROWS_PASS == 0, "tile shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    uint16_t* sW = reinterpret_cast<uint16_t*>(lds);                      // [2][TG_BN][TG_LD]
-    uint16_t* sA = sW + 2 * TG_BN * TG_LD;                                // [2][TG_BM][TG_LD]
+    uint16_t* sW = reinterpret_cast<uint16_t*>(lds);                      // [2][BN][TG_LD]
+    uint16_t* sA = sW + 2 * BN * TG_LD;                                   // [2][BM][TG_LD]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = wave >> 1, wm = wave & 1;
+    const int wn = wave / WM, wm = wave % WM;
     // XCD-aware tile order: the dispatcher deals consecutive workgroup ids to the 8 XCDs in turn; give each
     // XCD a contiguous range of tiles, m fastest, so that the tiles sharing weights share an L2
-    const int n_mt = (M + TG_BM - 1) / TG_BM, n_nt = (N + TG_BN - 1) / TG_BN, total = n_mt * n_nt;
+    const int n_mt = (M + BM - 1) / BM, n_nt = (N + BN - 1) / BN, total = n_mt * n_nt;
     int v = blockIdx.x;
     if (total % 8 == 0) v = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
-    const int n0 = (v / n_mt) * TG_BN, m0 = (v % n_mt) * TG_BM;
+    const int n0 = (v / n_mt) * BN, m0 = (v % n_mt) * BM;
 
-    // global -> register staging: every thread moves 4 x 16 bytes of each operand tile per k-step
-    const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;                  // 32 rows x 64 columns per pass
-    uint4 rw[4], ra[4];
-    auto load_tiles = [&](int k0) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = ld_row + 32 * p;
-            const int n = n0 + r, m = m0 + r;
-            rw[p] = n < N ? *reinterpret_cast<const uint4*>(W + (size_t)n * K + k0 + ld_col) : make_uint4(0, 0, 0, 0);
-            ra[p] = m < M ? *reinterpret_cast<const uint4*>(A + (size_t)m * K + k0 + ld_col) : make_uint4(0, 0, 0, 0);
-        }
+    // global -> register staging, 16 bytes per thread and pass
+    const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
+    // two register sets (0 and 1, separate arrays so that both stay in registers): while step kt is multiplied out
+    // of LDS, step kt + 1 waits in one set and step kt + 2 is being fetched into the other, so a global load has two
+    // steps' worth of time to arrive
+    static_assert(PW == 4 && PA == 4, "staging code below is written out for four passes per operand");
+    // (native vector types: a struct-typed uint4 would be copied through private memory)
+    struct StageW { u32x4 w0, w1, w2, w3; } sw0, sw1;   // weights: fetched two steps ahead (HBM latency)
+    struct StageA { u32x4 a0, a1, a2, a3; } sa;         // activations: one step ahead (they sit in L2)
+    // rows past the matrix are read from its last row (unconditional loads keep the memory pipeline's wait counts
+    // exact); what they produce is never stored
+    const int wrow_last = N - 1 - n0 - ld_row, arow_last = M - 1 - m0 - ld_row;   // clamp bounds relative to the thread's first row
+    const BF16* wbase = W + (size_t)(n0 + ld_row) * K + ld_col;
+    const BF16* abase = A + (size_t)(m0 + ld_row) * K + ld_col;
+    const BF16* wp0 = wbase + (ptrdiff_t)min(0 * ROWS_PASS, wrow_last) * K;
+    const BF16* wp1 = wbase + (ptrdiff_t)min(1 * ROWS_PASS, wrow_last) * K;
+    const BF16* wp2 = wbase + (ptrdiff_t)min(2 * ROWS_PASS, wrow_last) * K;
+    const BF16* wp3 = wbase + (ptrdiff_t)min(3 * ROWS_PASS, wrow_last) * K;
+    const BF16* ap0 = abase + (ptrdiff_t)min(0 * ROWS_PASS, arow_last) * K;
+    const BF16* ap1 = abase + (ptrdiff_t)min(1 * ROWS_PASS, arow_last) * K;
+    const BF16* ap2 = abase + (ptrdiff_t)min(2 * ROWS_PASS, arow_last) * K;
+    const BF16* ap3 = abase + (ptrdiff_t)min(3 * ROWS_PASS, arow_last) * K;
+    auto load_w = [&](StageW& s, int k0) __attribute__((always_inline)) {
+        s.w0 = *reinterpret_cast<const u32x4*>(wp0 + k0);
+        s.w1 = *reinterpret_cast<const u32x4*>(wp1 + k0);
+        s.w2 = *reinterpret_cast<const u32x4*>(wp2 + k0);
+        s.w3 = *reinterpret_cast<const u32x4*>(wp3 + k0);
     };
-    auto store_tiles = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = ld_row + 32 * p;
-            *reinterpret_cast<uint4*>(sW + (size_t)(buf * TG_BN + r) * TG_LD + ld_col) = rw[p];
-            *reinterpret_cast<uint4*>(sA + (size_t)(buf * TG_BM + r) * TG_LD + ld_col) = ra[p];
-        }
+    auto load_a = [&](StageA& s, int k0) __attribute__((always_inline)) {
+        s.a0 = *reinterpret_cast<const u32x4*>(ap0 + k0);
+        s.a1 = *reinterpret_cast<const u32x4*>(ap1 + k0);
+        s.a2 = *reinterpret_cast<const u32x4*>(ap2 + k0);
+        s.a3 = *reinterpret_cast<const u32x4*>(ap3 + k0);
     };
-    f32x16 acc[2][2];
+    auto store_wa = [&](const StageW& w, const StageA& a, int buf) __attribute__((always_inline)) {
+        uint16_t* dw = sW + (size_t)(buf * BN + ld_row) * TG_LD + ld_col;
+        uint16_t* da = sA + (size_t)(buf * BM + ld_row) * TG_LD + ld_col;
+        *reinterpret_cast<u32x4*>(dw + (size_t)0 * ROWS_PASS * TG_LD) = w.w0;
+        *reinterpret_cast<u32x4*>(dw + (size_t)1 * ROWS_PASS * TG_LD) = w.w1;
+        *reinterpret_cast<u32x4*>(dw + (size_t)2 * ROWS_PASS * TG_LD) = w.w2;
+        *reinterpret_cast<u32x4*>(dw + (size_t)3 * ROWS_PASS * TG_LD) = w.w3;
+        *reinterpret_cast<u32x4*>(da + (size_t)0 * ROWS_PASS * TG_LD) = a.a0;
+        *reinterpret_cast<u32x4*>(da + (size_t)1 * ROWS_PASS * TG_LD) = a.a1;
+        *reinterpret_cast<u32x4*>(da + (size_t)2 * ROWS_PASS * TG_LD) = a.a2;
+        *reinterpret_cast<u32x4*>(da + (size_t)3 * ROWS_PASS * TG_LD) = a.a3;
+    };
+    f32x16 acc[TI][TJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -89,48 +121,65 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, 
         nk = min(nk, kt_begin + per);
         outf += (size_t)blockIdx.y * M * N;
     }
-    if (kt_begin < nk) {
-        load_tiles(kt_begin * TG_BK);
-        store_tiles(kt_begin & 1);
-    }
-    __syncthreads();
-    for (int kt = kt_begin; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_tiles((kt + 1) * TG_BK);
-        const uint16_t* bw = sW + (size_t)(buf * TG_BN + wn * 64 + (lane & 31)) * TG_LD + 8 * (lane >> 5);
-        const uint16_t* ba = sA + (size_t)(buf * TG_BM + wm * 64 + (lane & 31)) * TG_LD + 8 * (lane >> 5);
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
+        const uint16_t* bw = sW + (size_t)(buf * BN + wn * SN + (lane & 31)) * TG_LD + 8 * (lane >> 5);
+        const uint16_t* ba = sA + (size_t)(buf * BM + wm * SM + (lane & 31)) * TG_LD + 8 * (lane >> 5);
 #pragma unroll
         for (int ks = 0; ks < TG_BK / 16; ++ks) {
-            bf16x8 fw[2], fa[2];
+            bf16x8 fw[TI], fa[TJ];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fw[i] = *reinterpret_cast<const bf16x8*>(bw + (size_t)i * 32 * TG_LD + ks * 16);
-                fa[i] = *reinterpret_cast<const bf16x8*>(ba + (size_t)i * 32 * TG_LD + ks * 16);
-            }
+            for (int i = 0; i < TI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(bw + (size_t)i * 32 * TG_LD + ks * 16);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < TJ; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(ba + (size_t)j * 32 * TG_LD + ks * 16);
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
         }
+    };
+    // one pipeline step: fetch the weights of kt + 2 and the activations of kt + 1, multiply kt out of LDS, then
+    // move kt + 1 (weights fetched a step earlier) into the other LDS buffer
+    if (kt_begin < nk) {
+        load_w(sw0, kt_begin * TG_BK);
+        load_a(sa, kt_begin * TG_BK);
+        store_wa(sw0, sa, 0);
+        if (kt_begin + 1 < nk) load_w(sw1, (kt_begin + 1) * TG_BK);
+    }
+    __syncthreads();
+    for (int kt = kt_begin; kt < nk; kt += 2) {
+        if (kt + 2 < nk) load_w(sw0, (kt + 2) * TG_BK);
+        if (kt + 1 < nk) load_a(sa, (kt + 1) * TG_BK);
+        multiply(0);
         if (kt + 1 < nk) {
-            store_tiles(buf ^ 1);     // the other buffer was last read before the previous barrier
+            store_wa(sw1, sa, 1);          // buffer 1 was last read before the previous barrier
             __syncthreads();
+            if (kt + 3 < nk) load_w(sw1, (kt + 3) * TG_BK);
+            if (kt + 2 < nk) load_a(sa, (kt + 2) * TG_BK);
+            multiply(1);
+            if (kt + 2 < nk) {
+                store_wa(sw0, sa, 0);
+                __syncthreads();
+            }
         }
     }
 
-    // ---- epilogue: acc[i][j][e] = out[m][n], n = n0 + 64 wn + 32 i + tile_row(e, lane), m = m0 + 64 wm + 32 j + lane % 32
+    // ---- epilogue: acc[i][j][e] = out[m][n], n = n0 + SN wn + 32 i + tile_row(e, lane), m = m0 + SM wm + 32 j + lane % 32
     if (EPI == TEPI_LMHEAD) {
-        __shared__ float s_bv[2][TG_BM];
-        __shared__ int32_t s_bi[2][TG_BM];
-        const int strip = n0 / TASC_LM_STRIP;
+        // a strip of TASC_LM_STRIP = 128 features is covered by SPW = 128 / SN consecutive wave rows (or by one)
+        constexpr int SPW = SN >= TASC_LM_STRIP ? 1 : TASC_LM_STRIP / SN;
+        static_assert(SN <= TASC_LM_STRIP || SN % TASC_LM_STRIP == 0, "wave span vs strip");
+        static_assert(SN <= TASC_LM_STRIP, "one strip per wave row at most");
+        __shared__ float s_bv[WN][BM];
+        __shared__ int32_t s_bi[WN][BM];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int ml = 64 * wm + 32 * j + (lane & 31), m = m0 + ml;
+        for (int j = 0; j < TJ; ++j) {
+            const int ml = SM * wm + 32 * j + (lane & 31), m = m0 + ml;
             float best = -INFINITY;
             int32_t best_i = 0x7FFFFFFF;
             if (m < M) {
+                const int strip = (n0 + SN * wn) / TASC_LM_STRIP;
                 float base = 0.f;
-                if (lm.bias.rowptr) {
+                if (lm.bias.rowptr && strip < lm.n_strips) {
                     const int u = lm.sel_tok[m];
                     base = lm.bias.base[u];
                     const int64_t r0 = lm.bias.rowptr[u];
@@ -138,21 +187,21 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, 
                     const int64_t be = r0 + lm.bias_ptr[(size_t)m * (lm.n_strips + 1) + strip + 1];
                     // the few seen successors of this row inside the strip: replace `base` by their own bias
                     for (int64_t p = bp; p < be; ++p) {
-                        const int nl = lm.bias.col[p] - n0 - 64 * wn;        // row within this wave's 64 features
-                        if (nl < 0 || nl >= 64) continue;
+                        const int nl = lm.bias.col[p] - n0 - SN * wn;        // row within this wave's span
+                        if (nl < 0 || nl >= SN) continue;
                         const float dv = lm.bias.val[p] - base;
 #pragma unroll
-                        for (int i = 0; i < 2; ++i)
+                        for (int i = 0; i < TI; ++i)
 #pragma unroll
                             for (int e = 0; e < 16; ++e)
                                 if (32 * i + tile_row(e, lane) == nl) acc[i][j][e] += dv;
                     }
                 }
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < TI; ++i) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        const int n = n0 + 64 * wn + 32 * i + tile_row(e, lane);
+                        const int n = n0 + SN * wn + 32 * i + tile_row(e, lane);
                         if (n < N) {
                             const float z = acc[i][j][e] + base;
                             if (lm.logits) lm.logits[(size_t)m * N + n] = z;
@@ -168,24 +217,34 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, 
             if (lane < 32) { s_bv[wn][ml] = best; s_bi[wn][ml] = best_i; }
         }
         __syncthreads();
-        if (tid < TG_BM && m0 + tid < M) {
-            float bv = s_bv[0][tid];
-            int32_t bi = s_bi[0][tid];
-            if (s_bv[1][tid] > bv || (s_bv[1][tid] == bv && s_bi[1][tid] < bi)) { bv = s_bv[1][tid]; bi = s_bi[1][tid]; }
-            lm.part_val[(size_t)(m0 + tid) * lm.n_strips + strip] = bv;
-            lm.part_idx[(size_t)(m0 + tid) * lm.n_strips + strip] = bi;
+        // one partial per (row, strip): merge the SPW wave rows of every strip of the tile
+        for (int idx = tid; idx < BM * (WN / SPW); idx += THREADS) {
+            const int ml = idx % BM, sg = idx / BM;
+            const int strip = (n0 + SN * sg * SPW) / TASC_LM_STRIP;
+            if (m0 + ml < M && strip < lm.n_strips) {
+                float bv = s_bv[sg * SPW][ml];
+                int32_t bi = s_bi[sg * SPW][ml];
+#pragma unroll
+                for (int q = 1; q < SPW; ++q) {
+                    const float ov = s_bv[sg * SPW + q][ml];
+                    const int32_t oi = s_bi[sg * SPW + q][ml];
+                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                }
+                lm.part_val[(size_t)(m0 + ml) * lm.n_strips + strip] = bv;
+                lm.part_idx[(size_t)(m0 + ml) * lm.n_strips + strip] = bi;
+            }
         }
         return;
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int m = m0 + 64 * wm + 32 * j + (lane & 31);
+    for (int j = 0; j < TJ; ++j) {
+        const int m = m0 + SM * wm + 32 * j + (lane & 31);
         if (m >= M) continue;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < TI; ++i) {
             if (EPI == TEPI_SWIGLU) {
                 // rows 0..15 of the 32-row tile are gate features, rows 16..31 the up rows of the same features
-                const int fbase = (n0 + 64 * wn + 32 * i) / 2;
+                const int fbase = (n0 + SN * wn + 32 * i) / 2;
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     const int f = fbase + 8 * q + 4 * (lane >> 5);
@@ -202,7 +261,7 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(const BF16* __restrict__ A, 
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + 64 * wn + 32 * i + 8 * q + 4 * (lane >> 5);
+                    const int n = n0 + SN * wn + 32 * i + 8 * q + 4 * (lane >> 5);
                     if (n < N) {
                         float4* p = reinterpret_cast<float4*>(outf + (size_t)m * N + n);
                         float4 vv = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
