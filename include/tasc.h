@@ -223,6 +223,7 @@ typedef struct {
     int64_t proposed;                    /* draft tokens proposed to live sequences                */
     int64_t accept_hist[TASC_MAX_K + 1]; /* number of (step, sequence) pairs per accept length     */
     double prefill_ms, decode_ms;        /* device time (HIP events on `stream`)                   */
+    int64_t xcd_local_steps;             /* steps whose layer phases synchronised through one XCD's L2 */
 } tasc_gen_stats;
 
 /*
@@ -256,10 +257,19 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
  *                        depend on these.
  *   TASC_CFG_TILED_PATH  bf16 forwards of more than 16 rows: 1 (default) = LDS-tiled MFMA kernels,
  *                        0 = the type-generic kernels.
+ *   TASC_CFG_SMALL_XCD_LOCAL
+ *                        1 (default) = when the layer phases' workgroups all run on one XCD (the
+ *                        kernel checks), their barriers exchange data through that XCD's L2 and
+ *                        skip the L2 write-back and invalidate; 0 = agent-scope barriers always.
+ *                        Results do not depend on it.
+ *   TASC_CFG_SMALL_LAYER_WORKERS
+ *                        in that XCD-local mode, how many of the layer workgroups compute; the
+ *                        others prefetch the next phase's weights into the XCD's L2 (0 = default,
+ *                        half of them).  Results do not depend on it.
  */
 enum {
     TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3,
-    TASC_CFG_TILED_PATH = 4
+    TASC_CFG_TILED_PATH = 4, TASC_CFG_SMALL_XCD_LOCAL = 5, TASC_CFG_SMALL_LAYER_WORKERS = 6
 };
 tasc_status tasc_config_set(int32_t key, int32_t value);
 

@@ -59,7 +59,8 @@ class SpecParams(C.Structure):
 
 class GenStats(C.Structure):
     _fields_ = [("steps", C.c_int64), ("emitted", C.c_int64), ("accepted", C.c_int64), ("proposed", C.c_int64),
-                ("accept_hist", C.c_int64 * (TASC_MAX_K + 1)), ("prefill_ms", C.c_double), ("decode_ms", C.c_double)]
+                ("accept_hist", C.c_int64 * (TASC_MAX_K + 1)), ("prefill_ms", C.c_double), ("decode_ms", C.c_double),
+                ("xcd_local_steps", C.c_int64)]
 
 
 _lib = None
@@ -320,6 +321,8 @@ def tasc_profile_read():
 
 
 TASC_CFG_SMALL_PATH, TASC_CFG_SMALL_GRID, TASC_CFG_SMALL_LAYER_WGS, TASC_CFG_SMALL_LAYER_STRIDE, TASC_CFG_TILED_PATH = 0, 1, 2, 3, 4
+TASC_CFG_SMALL_XCD_LOCAL = 5
+TASC_CFG_SMALL_LAYER_WORKERS = 6
 
 
 def tasc_config_set(key: int, value: int):

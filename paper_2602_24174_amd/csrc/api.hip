@@ -25,7 +25,7 @@ __global__ void k_reset(int B, int max_len, const int32_t* __restrict__ prompts,
         n_emit[b] = 0;
     }
     if (b == 0)
-        for (int i = threadIdx.x; i < 32; i += blockDim.x) counters[i] = 0;
+        for (int i = threadIdx.x; i < TASC_N_COUNTERS; i += blockDim.x) counters[i] = 0;
 }
 
 __global__ void k_check_prompts(const int32_t* __restrict__ prompts, int64_t n, int vocab, u64* flag) {
@@ -151,6 +151,20 @@ __global__ void k_init_block_tab(int B, int max_blocks, int32_t* bt) {
 }  // namespace
 
 // ================================================================ model
+// out (MFMA-fragment order, see TascLayerW) <- W [N][K] row-major bf16; rows N .. n_pad read as zero
+__global__ void k_repack_frag(const uint16_t* __restrict__ W, int N, int K, int n_pad, uint16_t* __restrict__ out) {
+    const int64_t chunk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte chunk per thread
+    const int nks = K / 32;
+    if (chunk >= (int64_t)(n_pad / 16) * nks * 64) return;
+    const int lane = (int)(chunk & 63);
+    const int64_t tile = chunk >> 6;
+    const int ks = (int)(tile % nks), nt = (int)(tile / nks);
+    const int row = nt * 16 + (lane & 15), col = ks * 32 + 8 * (lane >> 4);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < N) v = *reinterpret_cast<const uint4*>(W + (size_t)row * K + col);
+    *reinterpret_cast<uint4*>(out + chunk * 8) = v;
+}
+
 extern "C" tasc_status tasc_model_create(const tasc_model_desc* desc, const tasc_weight_ptrs* w, tasc_model** out) {
     TASC_REQUIRE(desc && w && out, "model_create: null argument");
     const tasc_model_desc& c = *desc;
@@ -188,9 +202,24 @@ extern "C" tasc_status tasc_model_create(const tasc_model_desc* desc, const tasc
         if (bytes) TASC_HIP(hipMemcpy(*p, src, bytes, hipMemcpyDefault));
         return TASC_OK;
     };
+    // fragment-order copies for the small-batch kernel, if the model has the shapes that kernel serves
+    const bool frag = c.dtype == TASC_BF16 && c.d_model % 32 == 0 && c.d_model <= 1536 && c.d_ffn % 32 == 0 && c.n_layers <= 48 &&
+                      (c.head_dim == 32 || c.head_dim == 64 || c.head_dim == 128);
+    auto dev_frag = [&](const void* src, size_t N, size_t K, const void** p) -> tasc_status {
+        const size_t n_pad = (N + 15) / 16 * 16;
+        void* q;
+        tasc_status rc2 = dev_alloc(n_pad * K * 2, &q);
+        if (rc2 != TASC_OK) return rc2;
+        const int64_t chunks = (int64_t)(n_pad / 16) * (K / 32) * 64;
+        k_repack_frag<<<dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, 0>>>((const uint16_t*)src, (int)N, (int)K, (int)n_pad, (uint16_t*)q);
+        TASC_LAUNCH_CHECK();
+        *p = q;
+        return TASC_OK;
+    };
     tasc_status rc;
     if ((rc = dev_copy(w->embed, (size_t)c.vocab * D * es, &m->embed)) != TASC_OK) return rc;
     if ((rc = dev_copy(w->lm_head, (size_t)c.vocab * D * es, &m->lm_head)) != TASC_OK) return rc;
+    if (frag && (rc = dev_frag(m->lm_head, c.vocab, D, (const void**)&m->lm_head_f)) != TASC_OK) return rc;
     if ((rc = dev_copy(w->gf, D * 4, (void**)&m->gf)) != TASC_OK) return rc;
     m->d_layers = nullptr;
     m->layers.resize(c.n_layers);
@@ -218,6 +247,13 @@ extern "C" tasc_status tasc_model_create(const tasc_model_desc* desc, const tasc
         L.g1 = (const float*)p;
         if ((rc = dev_copy(w->g2[l], D * 4, &p)) != TASC_OK) return rc;
         L.g2 = (const float*)p;
+        L.wqkv_f = L.wo_f = L.wgu_f = L.wd_f = nullptr;
+        if (frag) {
+            if ((rc = dev_frag(L.wqkv, HD + 2 * KD, D, &L.wqkv_f)) != TASC_OK) return rc;
+            if ((rc = dev_frag(L.wo, D, HD, &L.wo_f)) != TASC_OK) return rc;
+            if ((rc = dev_frag(L.wgu, 2 * F, D, &L.wgu_f)) != TASC_OK) return rc;
+            if ((rc = dev_frag(L.wd, D, F, &L.wd_f)) != TASC_OK) return rc;
+        }
     }
     if ((rc = dev_copy(m->layers.data(), sizeof(TascLayerW) * c.n_layers, (void**)&m->d_layers)) != TASC_OK) return rc;
     // RoPE table: angle(p, i) = p * theta^(-2i/hd), double on the host, fp32 on the device
@@ -273,7 +309,7 @@ WsLayout ws_layout(const tasc_model_desc& c, int B, int max_len, int max_rows) {
         (size_t)B * 4, (size_t)B * 4, (size_t)B * 4, (size_t)B * 4,  // n_tok n_prompt cached n_emit
         (size_t)B * max_blocks * 4,                                  // block_tab
         M * 4, (size_t)B * 4, (size_t)B * 4, M * 4, M * 4,           // row_tok n_rows pos0 sel_rows sel_tok
-        32 * 8,                                                      // counters
+        TASC_N_COUNTERS * 8,                                         // counters (+ barrier flags)
         M * c.d_model * 4,                                           // x
         M * std::max<size_t>(c.d_model, 1) * es,                     // h
         M * (HD + 2 * KD) * 4,                                       // qkv
@@ -336,7 +372,7 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     s->page_elems = 2 * (size_t)m->desc.n_kv_heads * TASC_KV_BLOCK * m->desc.head_dim;
     s->kv_layer_stride = (size_t)batch * s->max_blocks * s->page_elems;
     s->host_counters = nullptr;
-    s->bar_base = 0;
+    s->bar_epoch = 0;
     s->barb_base = 0;
     char* w = (char*)workspace;
     int i = 0;
@@ -370,7 +406,7 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     const int n = batch * s->max_blocks;
     k_init_block_tab<<<dim3((n + 255) / 256), dim3(256), 0, 0>>>(batch, s->max_blocks, d.block_tab);
     TASC_LAUNCH_CHECK();
-    TASC_HIP(hipMemsetAsync(d.counters, 0, 32 * sizeof(u64), 0));
+    TASC_HIP(hipMemsetAsync(d.counters, 0, TASC_N_COUNTERS * sizeof(u64), 0));
     // the MFMA attention multiplies masked keys by zero weights: the pool must never hold NaN or Inf patterns
     TASC_HIP(hipMemsetAsync(kv_pool, 0, need_kv, 0));
     TASC_HIP(hipDeviceSynchronize());
@@ -421,7 +457,7 @@ extern "C" tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s
     k_reset<<<dim3(B), dim3(256), 0, st>>>(B, s->max_len, d_prompts, d_off, d.tokens, d.n_tok, d.n_prompt, d.cached, d.n_emit,
                                            d.counters);
     TASC_LAUNCH_CHECK();
-    s->bar_base = 0;   // k_reset cleared the grid-barrier counters with the other counters
+    s->bar_epoch = 0;  // k_reset cleared the barrier flags and counters with the other counters
     s->barb_base = 0;
     k_check_prompts<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(d_prompts, total, m->desc.vocab, &d.counters[31]);
     TASC_LAUNCH_CHECK();
@@ -545,6 +581,7 @@ extern "C" tasc_status tasc_generate(const tasc_model* m, const tasc_ngram* ng, 
         stats->accepted = (int64_t)s->host_counters[3];
         stats->proposed = (int64_t)s->host_counters[4];
         for (int i = 0; i <= TASC_MAX_K; ++i) stats->accept_hist[i] = (int64_t)s->host_counters[8 + i];
+        stats->xcd_local_steps = (int64_t)s->host_counters[TASC_CTR_XCD_STEPS];
         float a = 0.f, b = 0.f;
         TASC_HIP(hipEventElapsedTime(&a, ev.e[0], ev.e[1]));
         TASC_HIP(hipEventElapsedTime(&b, ev.e[1], ev.e[2]));

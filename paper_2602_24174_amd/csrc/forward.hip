@@ -11,7 +11,7 @@
 #include "kernels_small.h"
 #include "kernels_tiled.h"
 
-TascConfig g_tasc_config = {2, 0, 0, 0, 1};
+TascConfig g_tasc_config = {2, 0, 0, 0, 1, 1, 0};
 static u64* g_phase_ts = nullptr;
 static int64_t g_phase_ts_cap = 0;
 
@@ -38,6 +38,12 @@ extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
     } else if (key == TASC_CFG_SMALL_LAYER_STRIDE) {
         TASC_REQUIRE(value >= 0 && value <= 64, "config_set: layer stride %d outside [0, 64]", value);
         g_tasc_config.layer_stride = value;
+    } else if (key == TASC_CFG_SMALL_LAYER_WORKERS) {
+        TASC_REQUIRE(value >= 0 && value <= 64, "config_set: layer workers %d outside [0, 64]", value);
+        g_tasc_config.layer_workers = value;
+    } else if (key == TASC_CFG_SMALL_XCD_LOCAL) {
+        TASC_REQUIRE(value == 0 || value == 1, "config_set: XCD-local switch %d outside [0, 1]", value);
+        g_tasc_config.xcd_local = value;
     } else {
         tasc_set_error("config_set: unknown key %d", key);
         return TASC_EINVAL;
@@ -275,8 +281,9 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
 }
 
 // the fused small-batch kernel serves a bf16 forward of at most 16 rows with these shapes
-bool small_path_fits(const tasc_model_desc& c, int batch, int nq) {
-    return c.dtype == TASC_BF16 && batch * nq <= SMALL_ROWS && c.d_model <= SMALL_KC && c.d_model % 32 == 0 &&
+bool small_path_fits(const tasc_model* m, int batch, int nq, int max_blocks) {
+    const tasc_model_desc& c = m->desc;
+    return m->lm_head_f != nullptr && c.dtype == TASC_BF16 && batch * nq <= SMALL_ROWS && c.n_layers <= SMALL_MAX_LAYERS && batch * max_blocks <= SMALL_MAX_BT && c.d_model <= SMALL_KC && c.d_model % 32 == 0 &&
            (c.head_dim == 32 || c.head_dim == 64 || c.head_dim == 128) && c.d_ffn % 32 == 0 && c.vocab >= 16 &&
            (nq * (c.n_heads / c.n_kv_heads)) >= 1;
 }
@@ -308,7 +315,7 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     SmallArgs a;
     a.layers = m->d_layers;
     a.embed = (const BF16*)m->embed;
-    a.lm_head = (const BF16*)m->lm_head;
+    a.lm_head = (const BF16*)m->lm_head_f;
     a.gf = m->gf;
     a.rope_cos = m->rope_cos;
     a.rope_sin = m->rope_sin;
@@ -328,9 +335,11 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     a.accept_len = tail ? tail->accept_len : nullptr;
     a.emitted = tail ? tail->emitted : nullptr;
     a.trace_step = tail ? tail->trace_step : nullptr;
-    a.bar_counter = &d.counters[TASC_CTR_BAR];
+    a.bar_flags = (u32*)&d.counters[TASC_CTR_FLAGS];
     a.barb_counter = &d.counters[TASC_CTR_BARB];
     a.bar_error = (u32*)&d.counters[TASC_CTR_BAR_ERR];
+    a.xcc_mask = (u32*)&d.counters[TASC_CTR_XCC];
+    a.xcd_local = g_tasc_config.xcd_local;
     a.bias_ptr = d.bias_ptr;
     const int n_phases = 3 + 5 * c.n_layers, n_lg_phases = 1 + 5 * c.n_layers;
     a.phase_ts = g_phase_ts;
@@ -338,16 +347,21 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     const int last = n_sel > 0 ? n_phases : n_lg_phases;   // without LM-head rows the step ends after the last layer
     int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
     grid = grid < g_cu_count ? grid : g_cu_count;            // every workgroup must be resident: at most one per compute unit
-    // layer group: by default the first 48 workgroups, which the dispatcher spreads over all XCDs (fewer
-    // participants make the barriers of the 150 latency-bound layer phases cheaper, and a phase has at most
-    // 96 work items anyway; the LM head uses the whole grid)
-    int stride = g_tasc_config.layer_stride > 0 ? g_tasc_config.layer_stride : 1;
-    int lg = g_tasc_config.layer_wgs > 0 ? g_tasc_config.layer_wgs : 48;
+    // Layer group.  The dispatcher deals workgroup ids round-robin over the 8 XCDs, so by default the group is
+    // every 8th workgroup, 32 of them: one XCD's worth, which lets the 150 latency-bound layer phases hand
+    // their activations over through that XCD's L2 (the kernel checks where it really runs and falls back
+    // to agent-scope barriers otherwise).  With XCD-local barriers off, or a grid too small for that, the
+    // group is the first 48 workgroups, spread over all XCDs.  The LM head always uses the whole grid.
+    const bool one_xcd = g_tasc_config.xcd_local != 0 && g_tasc_config.small_path == 2 && grid >= 8 * 32;
+    int stride = g_tasc_config.layer_stride > 0 ? g_tasc_config.layer_stride : (one_xcd ? 8 : 1);
+    int lg = g_tasc_config.layer_wgs > 0 ? g_tasc_config.layer_wgs : (one_xcd && g_tasc_config.layer_stride <= 0 ? 32 : 48);
     if (stride > grid) stride = grid;
     if (lg > (grid + stride - 1) / stride) lg = (grid + stride - 1) / stride;
+    if (lg > SMALL_MAX_GROUP) lg = SMALL_MAX_GROUP;
     a.lg_stride = stride;
     a.lg_count = lg;
-    a.bar_base = s->bar_base;
+    a.lg_workers = g_tasc_config.layer_workers > 0 ? g_tasc_config.layer_workers : lg;
+    a.bar_epoch = s->bar_epoch;
     a.barb_base = s->barb_base;
     PROF(TASC_KC_LAYERS);
     auto launch = [&](int p0, int p1) {
@@ -357,7 +371,7 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     };
     if (g_tasc_config.small_path == 2) {
         launch(0, last);
-        s->bar_base += (u64)(n_lg_phases - 1) * lg;
+        s->bar_epoch += (u32)(n_lg_phases - 1);
         s->barb_base += (u64)(last - n_lg_phases) * grid;
     } else {
         for (int ph = 0; ph < last; ++ph) {
@@ -379,7 +393,7 @@ tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, 
     // call's row count, so that a greedy step and a speculative step of one session use the same kernels and
     // reduce every row in the same order.  Prompt chunks of more than 16 rows always take the tiled kernels.
     const int decode_rows = s->max_rows < SMALL_ROWS ? s->max_rows : SMALL_ROWS;
-    if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m->desc, s->batch, decode_rows))
+    if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m, s->batch, decode_rows, s->max_blocks))
         return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);
     if (g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc)) return forward_tiled(m, s, nq, n_sel, logits_dbg, st);
     if (m->desc.dtype == TASC_F32) return forward_generic<float>(m, s, nq, n_sel, logits_dbg, st);

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
                             const float g = acc[i][j][4 * q + u], up = acc[i][j][8 + 4 * q + u];
                             o[u] = g / (1.0f + __expf(-g)) * up;
                         }
-                        *reinterpret_cast<uint2*>(outb + (size_t)m * (N / 2) + f) = pack_bf16x4(o[0], o[1], o[2], o[3]);
+                        *reinterpret_cast<u32x2*>(outb + (size_t)m * (N / 2) + f) = pack_bf16x4(o[0], o[1], o[2], o[3]);
                     }
                 }
             } else {
@@ -329,8 +329,9 @@ struct AttnArgs {
 };
 
 template <int NKS>
+#define TILED_ATT_SLOT 2048           // floats of one attention combine slot (rows of a pass x head_dim)
 __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) float s_buf[4 * SMALL_ATT_SLOT + 4 * 32 * 2];
+    __shared__ __attribute__((aligned(16))) float s_buf[4 * TILED_ATT_SLOT + 4 * 32 * 2];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr int hd = 32 * NKS, ndt = 2 * NKS;
     constexpr int RT = NKS <= 2 ? 2 : 1, rows_pass = 16 * RT;
@@ -338,7 +339,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
     const int R = a.nq * Gq;
     const size_t v_off = (size_t)a.Hkv * TASC_KV_BLOCK * hd;
     const int m = lane & 15, qd = lane >> 4;
-    float* slot_ml = s_buf + 4 * SMALL_ATT_SLOT;
+    float* slot_ml = s_buf + 4 * TILED_ATT_SLOT;
     const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv;
     const int r0 = blockIdx.y * rows_pass;
     const int nr = a.n_rows[b], p0 = a.pos0[b];
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
         }
     }
     auto merge_round = [&](bool writer, bool reader, int sl) {
-        float* so = s_buf + sl * SMALL_ATT_SLOT;
+        float* so = s_buf + sl * TILED_ATT_SLOT;
         if (writer) {
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
@@ -484,7 +485,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
                 BF16* op = a.att + (size_t)(b * a.nq + i) * a.H * hd + (size_t)(g * Gq + jq) * hd;
 #pragma unroll
                 for (int dt = 0; dt < ndt; ++dt)
-                    *reinterpret_cast<uint2*>(op + 16 * dt + 4 * qd) =
+                    *reinterpret_cast<u32x2*>(op + 16 * dt + 4 * qd) =
                         pack_bf16x4(o[rt][dt][0] * inv, o[rt][dt][1] * inv, o[rt][dt][2] * inv, o[rt][dt][3] * inv);
             }
         }

@@ -108,10 +108,19 @@ struct TascLayerW {
     const void* wd;    // [d, F]
     const float* g1;
     const float* g2;
+    // The same four matrices in MFMA-fragment order for the small-batch kernel (nullptr if the model is not
+    // eligible): tile (nt, ks) = rows 16 nt .. +16, columns 32 ks .. +32 is one contiguous KB, lane l of a wave
+    // owning the 8 elements W[16 nt + (l & 15)][32 ks + 8 (l >> 4) .. +8]; tiles ordered [nt][ks].  A wave
+    // instruction that loads one A fragment per lane then reads 8 whole cache lines instead of 16 half lines.
+    const void* wqkv_f;
+    const void* wo_f;
+    const void* wgu_f;
+    const void* wd_f;
 };
 
 struct tasc_model {
     tasc_model_desc desc;
+    void* lm_head_f = nullptr;   // LM head in MFMA-fragment order (rows padded to a multiple of 16), or nullptr
     std::vector<TascLayerW> layers;
     void* embed;
     void* lm_head;
@@ -173,14 +182,17 @@ struct tasc_session {
     size_t page_elems;        // elements per page (K and V)
     TascSessDev d;
     u64* host_counters;       // pinned
-    u64 bar_base;             // arrivals the layer-group barrier counter (counters[24]) has seen so far
+    u32 bar_epoch;            // barriers the layer group's arrival flags (counters[32..63]) have seen so far
     u64 barb_base;            // same for the whole-grid barrier counter (counters[26])
 };
 
 // counters[] slots used beyond the statistics
-#define TASC_CTR_BAR 24       // grid-barrier arrival counter
+#define TASC_CTR_FLAGS 32     // 64 32-bit arrival flags of the layer-group barrier (slots 32..63)
+#define TASC_N_COUNTERS 64
 #define TASC_CTR_BAR_ERR 25   // grid-barrier time-out flag (low 32 bits)
 #define TASC_CTR_BARB 26      // whole-grid barrier arrival counter
+#define TASC_CTR_XCD_STEPS 28 // steps of the persistent kernel whose layer group used XCD-local barriers
+#define TASC_CTR_XCC 27       // XCDs the layer group of the running step found itself on (low 32 bits)
 
 // the tail of a verify step, fused into the forward when the small-batch kernel runs it
 struct TascVerifyTail {
@@ -198,6 +210,8 @@ struct TascConfig {
     int small_grid;           // workgroups of the persistent kernel (0 = one per compute unit)
     int layer_wgs;            // workgroups of its layer group (0 = default)
     int layer_stride;         // the group's workgroup-id stride (0 = default)
+    int xcd_local;            // 1 = the layer group may use XCD-local barriers when it sits on one XCD
+    int layer_workers;        // members of the layer group that compute in XCD-local mode (0 = half), the rest prefetch
     int tiled_path;           // 1: LDS-tiled MFMA kernels for bf16 forwards of more than 16 rows, 0: generic kernels
 };
 extern TascConfig g_tasc_config;

@@ -25,6 +25,8 @@ def main():
     ap.add_argument("--layer-wgs", type=int, default=0)
     ap.add_argument("--layer-stride", type=int, default=0)
     ap.add_argument("--max-rows", type=int, default=16)
+    ap.add_argument("--workers", type=int, default=0, help="computing members of the layer group in XCD-local mode (0 = half)")
+    ap.add_argument("--agent-barriers", action="store_true", help="agent-scope barriers only (no XCD-local mode)")
     args = ap.parse_args()
     import torch
     import workload as W
@@ -40,6 +42,8 @@ def main():
     model = T.tasc_model_create(cfg, weights, max_len)
     ng = T.tasc_ngram_build(corpus[0], corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
     sess = T.tasc_session_create(model, cfg.batch, max_len, args.max_rows)
+    T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 0 if args.agent_barriers else 1)
+    T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WORKERS, args.workers)
     T.tasc_config_set(T.TASC_CFG_SMALL_GRID, args.grid)
     T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WGS, args.layer_wgs)
     T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_STRIDE, args.layer_stride)
@@ -59,16 +63,20 @@ def main():
     T.tasc_profile_phases(None)
 
     ts = buf.cpu().numpy().reshape(n_wg, n_ph, 2).astype(np.float64) / 100.0      # microseconds (100 MHz clock)
-    stride, lg = args.layer_stride or 1, args.layer_wgs or 48
+    one_xcd = not args.agent_barriers and n_wg >= 256            # the library's defaults
+    stride = args.layer_stride or (8 if one_xcd else 1)
+    lg = args.layer_wgs or (32 if one_xcd and not args.layer_stride else 48)
     members = [w for w in range(n_wg) if w % stride == 0 and w // stride < lg]
-    lay = ts[members][:, :1 + 5 * cfg.n_layers]
+    n_work = (args.workers or lg) if one_xcd else lg
+    pre = ts[members[n_work:]][:, :1 + 5 * cfg.n_layers]
+    lay = ts[members[:n_work]][:, :1 + 5 * cfg.n_layers]
     begin, end = lay[:, :, 0], lay[:, :, 1]
     work = (end - begin).max(axis=0)
     span = end.max(axis=0) - begin.min(axis=0)
     gap = np.append(begin.min(axis=0)[1:] - end.max(axis=0)[:-1], 0.0)
     per = lambda v: np.round(np.median(v[1:].reshape(cfg.n_layers, 5), axis=0), 2)
     t0 = begin.min()
-    print(f"{cfg.name}: grid {n_wg} workgroups, layer group {len(members)} (stride {stride}); k = {cfg.k}, cached length "
+    print(f"{cfg.name}: grid {n_wg} workgroups, layer group {len(members)} (stride {stride}), {n_work} of them computing; k = {cfg.k}, cached length "
           f"about {cfg.prompt_len + 6 * (cfg.k + 1)}")
     print(f"whole step {ts[:, :, 1].max() - t0:.1f} us; embedding + layers {end.max() - t0:.1f} us; "
           f"LM head {ts[:, -2, 1].max() - ts[:, -2, 0].min():.1f} us; accept {ts[0, -1, 1] - ts[0, -1, 0]:.1f} us")
@@ -76,6 +84,8 @@ def main():
     print("  longest workgroup's work                 ", per(work))
     print("  first begin .. last end                  ", per(span))
     print("  barrier: last end -> next phase's begin  ", per(gap))
+    if len(pre):
+        print(f"  prefetchers ({len(pre)}): longest fetch-ahead      ", per((pre[:, :, 1] - pre[:, :, 0]).max(axis=0)))
 
 
 if __name__ == "__main__":

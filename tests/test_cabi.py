@@ -35,4 +35,4 @@ def test_binding_structs_match_header_sizes():
     assert ctypes.sizeof(T.ModelDesc) == 11 * 4
     assert ctypes.sizeof(T.SpecParams) == 16
     assert ctypes.sizeof(T.NgramStats) == 8 + 4 * 9 * 8 + 16
-    assert ctypes.sizeof(T.GenStats) == 4 * 8 + 16 * 8 + 16
+    assert ctypes.sizeof(T.GenStats) == 4 * 8 + 16 * 8 + 16 + 8

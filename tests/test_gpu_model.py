@@ -180,7 +180,8 @@ def test_api_errors():
 @pytest.mark.parametrize("heads", [(6, 2, 32), (4, 2, 64), (2, 1, 128), (4, 4, 64)])
 def test_small_batch_fused_kernel(heads):
     """bf16 forwards of at most 16 rows run in the fused persistent kernel: against the oracle, against the
-    same kernel launched phase by phase (bit-identical), and speculative == greedy within each mode."""
+    same kernel launched phase by phase and with agent-scope barriers only (bit-identical), and speculative ==
+    greedy within each mode."""
     import torch
     import paper_2602_24174_amd as T
     from gpu_util import Rig
@@ -198,9 +199,10 @@ def test_small_batch_fused_kernel(heads):
     om = OM.OracleModel(cfg, rig.weights)
     results = {}
     try:
-        for mode in (2, 1, 0):
+        for mode in (2, 3, 1, 0):                  # 3 = persistent kernel with agent-scope barriers only
             print(f"heads {heads} mode {mode}", flush=True)
-            T.tasc_config_set(T.TASC_CFG_SMALL_PATH, mode)
+            T.tasc_config_set(T.TASC_CFG_SMALL_PATH, min(mode, 2))
+            T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 0 if mode == 3 else 1)
             out, st, tr = rig.generate(trace_steps=cfg.gen_len)
             g_out, g_st, _ = rig.generate(k=0)
             assert (out == g_out).all(), f"mode {mode}: speculative output differs from greedy"
@@ -234,8 +236,11 @@ def test_small_batch_fused_kernel(heads):
             results[mode] = (out, tr, np.stack(all_logits))
     finally:
         T.tasc_config_set(T.TASC_CFG_SMALL_PATH, 2)
-    assert (results[1][0] == results[2][0]).all() and (results[1][1] == results[2][1]).all()
-    assert (results[1][2] == results[2][2]).all(), "persistent and per-phase launches must be bit-identical"
+        T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 1)
+    for other in (1, 3):
+        assert (results[other][0] == results[2][0]).all() and (results[other][1] == results[2][1]).all()
+        assert (results[other][2] == results[2][2]).all(), "persistent (XCD-local or agent-scope barriers) and " \
+            "per-phase launches must be bit-identical"
 
 
 @pytest.mark.parametrize("heads", [(4, 2, 64), (2, 1, 128), (6, 2, 32)])
