@@ -264,8 +264,8 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
  *                        Results do not depend on it.
  *   TASC_CFG_SMALL_LAYER_WORKERS
  *                        in that XCD-local mode, how many of the layer workgroups compute; the
- *                        others prefetch the next phase's weights into the XCD's L2 (0 = default,
- *                        half of them).  Results do not depend on it.
+ *                        others prefetch the next phase's weights into the XCD's L2 (0 = default:
+ *                        all compute).  Results do not depend on it.
  */
 enum {
     TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3,

@@ -11,7 +11,8 @@
 #include "kernels_small.h"
 #include "kernels_tiled.h"
 
-TascConfig g_tasc_config = {2, 0, 0, 0, 1, 1, 0};
+TascConfig g_tasc_config = {/*small_path*/ 2, /*small_grid*/ 0, /*layer_wgs*/ 0, /*layer_stride*/ 0, /*tiled_path*/ 1, /*xcd_local*/ 1,
+                             /*layer_workers*/ 0};
 static u64* g_phase_ts = nullptr;
 static int64_t g_phase_ts_cap = 0;
 

@@ -210,9 +210,9 @@ struct TascConfig {
     int small_grid;           // workgroups of the persistent kernel (0 = one per compute unit)
     int layer_wgs;            // workgroups of its layer group (0 = default)
     int layer_stride;         // the group's workgroup-id stride (0 = default)
-    int xcd_local;            // 1 = the layer group may use XCD-local barriers when it sits on one XCD
-    int layer_workers;        // members of the layer group that compute in XCD-local mode (0 = half), the rest prefetch
     int tiled_path;           // 1: LDS-tiled MFMA kernels for bf16 forwards of more than 16 rows, 0: generic kernels
+    int xcd_local;            // 1 = the layer group may use XCD-local barriers when it sits on one XCD
+    int layer_workers;        // members of the layer group that compute in XCD-local mode (0 = all), the rest prefetch
 };
 extern TascConfig g_tasc_config;
 
