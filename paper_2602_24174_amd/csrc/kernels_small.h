@@ -268,13 +268,13 @@ __device__ __forceinline__ void stage_normed_issue(const GAS float* x, const GAS
 #pragma unroll
         for (int t = 0; t < NTC; ++t) {
             const int c = 4 * (lane + 64 * t);
-            if (t < nt) rg.v[j][t] = ld_l2_f4(xr + (c < D ? c : D - 4));
+            rg.v[j][t] = ld_l2_f4(xr + (c < D ? c : D - 4));        // unconditional, see load_w
         }
     }
 #pragma unroll
     for (int t = 0; t < NTC; ++t) {
         const int c = 4 * (lane + 64 * t);
-        if (t < nt) rg.g[t] = gld<f32x4>(g + (c < D ? c : D - 4));
+        rg.g[t] = gld<f32x4>(g + (c < D ? c : D - 4));
     }
 }
 template <int NTC>
@@ -370,13 +370,15 @@ template <int NT, int WKS>
 __device__ __forceinline__ void load_w(const GAS BF16* (&wtile)[NT], int kc0, int nks, bf16x8 (&w)[NT][WKS]) {
     const int lane = threadIdx.x & 63, wave = wave_id();
     const size_t woff = (size_t)(kc0 / 32) * 512 + lane * 8;
+    // No load sits under a condition (a conditional load ends in a register copy at the join, and the copy waits
+    // for the data: the loads would complete one by one): a slot beyond the chunk reloads the wave's first k-step,
+    // which its L1 already holds or is fetching.
 #pragma unroll
     for (int u = 0; u < WKS; ++u) {
         const int ks = wave + SMALL_NW * u;
-        if (ks < nks) {
+        const int ksc = ks < nks ? ks : (wave < nks ? wave : 0);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) w[t][u] = gld<bf16x8>(wtile[t] + woff + (size_t)ks * 512);
-        }
+        for (int t = 0; t < NT; ++t) w[t][u] = gld<bf16x8>(wtile[t] + woff + (size_t)ksc * 512);
     }
 }
 template <int NT, int WKS>
@@ -798,7 +800,7 @@ __device__ __forceinline__ void phase_lmhead(const SmallArgs& a, int wg, int nwg
         bf16x8 w[WG_KS];
 #pragma unroll
         for (int u = 0; u < WG_KS; ++u)
-            if (u < nks) w[u] = gld<bf16x8>(wrow + (size_t)u * 512);
+            w[u] = gld<bf16x8>(wrow + (size_t)min(u, nks - 1) * 512);   // unconditional, see load_w
         const bool own = live && m < a.n_sel;
         int64_t bp = 0, be = 0;
         float base = 0.f;
@@ -826,8 +828,7 @@ __device__ __forceinline__ void phase_lmhead(const SmallArgs& a, int wg, int nwg
             }
             if (ks0 + WG_KS < nks) {
 #pragma unroll
-                for (int u = 0; u < WG_KS; ++u)
-                    if (ks0 + WG_KS + u < nks) w[u] = gld<bf16x8>(wrow + (size_t)(ks0 + WG_KS + u) * 512);
+                for (int u = 0; u < WG_KS; ++u) w[u] = gld<bf16x8>(wrow + (size_t)min(ks0 + WG_KS + u, nks - 1) * 512);
             }
         }
         float best = -INFINITY;
