@@ -204,6 +204,7 @@ def main():
         "value_basis": "emitted tokens (accepted drafts + bonus) / decode-loop device time; the step also holds build and prefill",
         "phases_ms": {"ngram_build": build_ms, "prefill": prefill_ms, "decode": decode_ms / args.steps},
         "verify_steps_per_generate": vsteps / args.steps,
+        "xcd_local_steps_per_generate": sum(s.xcd_local_steps for s, _ in stats) / args.steps,
         "mean_accept_len": accepted / max(1, vsteps * cfg.batch),
         "accepted_draft_tokens_per_s": accepted / (decode_ms / 1e3),
         "accept_hist": hist, "proposed": proposed,

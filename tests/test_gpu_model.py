@@ -199,10 +199,12 @@ def test_small_batch_fused_kernel(heads):
     om = OM.OracleModel(cfg, rig.weights)
     results = {}
     try:
-        for mode in (2, 3, 1, 0):                  # 3 = persistent kernel with agent-scope barriers only
+        # 3 = persistent kernel with agent-scope barriers only, 4 = half of the layer group prefetching
+        for mode in (2, 3, 4, 1, 0):
             print(f"heads {heads} mode {mode}", flush=True)
             T.tasc_config_set(T.TASC_CFG_SMALL_PATH, min(mode, 2))
             T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 0 if mode == 3 else 1)
+            T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WORKERS, 16 if mode == 4 else 0)
             out, st, tr = rig.generate(trace_steps=cfg.gen_len)
             g_out, g_st, _ = rig.generate(k=0)
             assert (out == g_out).all(), f"mode {mode}: speculative output differs from greedy"
@@ -231,13 +233,18 @@ def test_small_batch_fused_kernel(heads):
                     worst = max(worst, float(np.abs(got[b].astype(np.float64) - z).max()))
                     after = T.tasc_session_get_tokens(rig.session, b)
                     caches[b].length += len(after) - len(before[b])
-            print(f"mode {mode}: max |logit - oracle| = {worst:.3e}, steps {st.steps}", flush=True)
+            print(f"mode {mode}: max |logit - oracle| = {worst:.3e}, steps {st.steps}, XCD-local steps {st.xcd_local_steps}", flush=True)
+            if mode in (2, 4):
+                assert st.xcd_local_steps > 0, "the layer group was expected to run on one XCD"
+            if mode == 3:
+                assert st.xcd_local_steps == 0
             assert worst <= 5e-2
             results[mode] = (out, tr, np.stack(all_logits))
     finally:
         T.tasc_config_set(T.TASC_CFG_SMALL_PATH, 2)
         T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 1)
-    for other in (1, 3):
+        T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WORKERS, 0)
+    for other in (1, 3, 4):
         assert (results[other][0] == results[2][0]).all() and (results[other][1] == results[2][1]).all()
         assert (results[other][2] == results[2][2]).all(), "persistent (XCD-local or agent-scope barriers) and " \
             "per-phase launches must be bit-identical"
