@@ -29,13 +29,39 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__global__ void k_unigram(const int32_t* __restrict__ tok, u64 T, int vocab, u32* hist, u32* bad) {
-    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-    u64 stride = (u64)gridDim.x * blockDim.x;
-    for (; i < T; i += stride) {
-        int t = tok[i];
-        if (t < 0 || t >= vocab) atomicOr(bad, 1u);
-        else atomicAdd(&hist[t], 1u);
+// Token histogram.  Corpus tokens follow a steep rank-frequency law, so adding every occurrence straight to the
+// global histogram serialises on the few hottest counters.  A workgroup therefore first counts a chunk of
+// kUniChunk tokens in an LDS table (open addressing, twice as many slots as tokens, so it cannot fill up) and
+// then adds each distinct token's count to the global histogram once.
+constexpr int kUniChunk = 2048, kUniSlots = 4096;
+__global__ __launch_bounds__(kThreads) void k_unigram(const int32_t* __restrict__ tok, u64 T, int vocab, u32* hist, u32* bad) {
+    __shared__ u32 s_key[kUniSlots];
+    __shared__ u32 s_cnt[kUniSlots];
+    for (int i = threadIdx.x; i < kUniSlots; i += kThreads) { s_key[i] = 0xFFFFFFFFu; s_cnt[i] = 0; }
+    __syncthreads();
+    for (u64 c0 = (u64)blockIdx.x * kUniChunk; c0 < T; c0 += (u64)gridDim.x * kUniChunk) {
+        for (int j = threadIdx.x; j < kUniChunk; j += kThreads) {
+            const u64 i = c0 + j;
+            if (i >= T) break;
+            const int t = tok[i];
+            if (t < 0 || t >= vocab) { atomicOr(bad, 1u); continue; }
+            u32 h = ((u32)t * 2654435761u) >> 20;                      // top 12 bits: kUniSlots = 4096
+            for (;;) {
+                const u32 old = atomicCAS(&s_key[h], 0xFFFFFFFFu, (u32)t);
+                if (old == 0xFFFFFFFFu || old == (u32)t) { atomicAdd(&s_cnt[h], 1u); break; }
+                h = (h + 1) & (kUniSlots - 1);
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < kUniSlots; i += kThreads) {
+            const u32 k = s_key[i];
+            if (k != 0xFFFFFFFFu) {
+                atomicAdd(&hist[k], s_cnt[i]);
+                s_key[i] = 0xFFFFFFFFu;
+                s_cnt[i] = 0;
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -328,7 +354,7 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
     u64 h_counters[8];
 
     if (T > 0) {
-        unsigned grid = (unsigned)std::min<u64>((T + kThreads - 1) / kThreads, 1u << 16);
+        unsigned grid = (unsigned)std::min<u64>((T + kUniChunk - 1) / kUniChunk, 2048);
         k_unigram<<<dim3(grid), dim3(kThreads), 0, st>>>(d_tok, T, vocab, ng->unigram, (u32*)&d_counters[4]);
         TASC_LAUNCH_CHECK();
         k_unigram_argmax<<<dim3(64), dim3(kThreads), 0, st>>>(ng->unigram, vocab, &d_counters[3]);
