@@ -61,6 +61,21 @@ __device__ __forceinline__ void gst(GAS T* p, V v) {
 // not lane masks, around the loads it guards)
 __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
+// Sum over the 64 lanes with DPP row operations (a few cycles each; the ds_bpermute path of __shfl_xor costs an LDS
+// round trip per step).  The lanes are added in a fixed order, the same for every call.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));   // row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));   // row_mirror
+    // every lane now holds the sum of its row of 16; rows 0..3 are lanes 0-15, 16-31, 32-47, 48-63
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
 #define SMALL_ROWS 16
 #define SMALL_KC 1536                 // activation columns staged in LDS at a time
 #define SMALL_KP (SMALL_KC + 8)       // padded LDS row length (elements)
@@ -291,7 +306,7 @@ __device__ __forceinline__ void stage_normed_finish(const NormRegs<NTC>& rg, int
                 const float s4 = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
                 ss[j] += 4 * (lane + 64 * t) < D ? s4 : 0.f;
             }
-        ss[j] = wave_sum(ss[j]);
+        ss[j] = wave_sum_dpp(ss[j]);
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -437,6 +452,7 @@ __device__ __forceinline__ u32 phase_qkv(const SmallArgs& a, const SmallTabs& tb
     u32 sink = 0;
     NormRegs<WKS> xr;                             // WKS = 3: D <= 768; WKS = 6: D <= 1536
     stage_normed_issue<WKS>(gptr(a.x), gptr(L.g1), nullptr, a.M, a.D, xr);
+    __builtin_amdgcn_s_barrier();                 // every wave's activation loads are queued before any weight load
     bool staged = false;
     for (int base = wg; base < n_items; base += nwg * NI) {
         const GAS BF16* wrow[2 * NI];
@@ -526,6 +542,7 @@ __device__ __forceinline__ u32 phase_proj_resid(const SmallArgs& a, const GAS BF
     u32 sink = 0;
     CopyRegs<WKS> cr;                             // WKS = 3: chunks of at most 768 columns; WKS = 6: 1536
     stage_copy_issue<WKS>(src, a.M, K, 0, min(SMALL_KC, K), cr);
+    __builtin_amdgcn_s_barrier();                 // every wave's activation loads are queued before any weight load
     bool staged = false;
     for (int base = wg; base < n_items; base += nwg * NI) {
         const GAS BF16* wrow[NI];
@@ -579,6 +596,7 @@ __device__ __forceinline__ u32 phase_gate_up(const SmallArgs& a, const SmallTabs
     u32 sink = 0;
     NormRegs<WKS> xr;
     stage_normed_issue<WKS>(gptr(a.x), gptr(L.g2), nullptr, a.M, a.D, xr);
+    __builtin_amdgcn_s_barrier();                 // every wave's activation loads are queued before any weight load
     bool staged = false;
     for (int base = wg; base < n_items; base += nwg * NI) {
         const GAS BF16* wrow[2 * NI];
