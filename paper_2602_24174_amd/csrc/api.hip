@@ -319,6 +319,7 @@ WsLayout ws_layout(const tasc_model_desc& c, int B, int max_len, int max_rows) {
         8 * M * std::max<size_t>(HD + 2 * KD, c.d_model) * 4,        // att_part: k-slice partial sums of the narrow GEMMs
         (size_t)B * TASC_MAX_K * 4,                                  // drafts
         M * (n_strips + 1) * 4,                                      // bias_ptr
+        tasc_small_ws_bytes(c),                                      // write-once activation buffers of the small-batch kernel
     };
     WsLayout L;
     size_t o = 0;
@@ -401,6 +402,7 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     d.att_part = (float*)(w + L.off[i++]);
     d.drafts = (int32_t*)(w + L.off[i++]);
     d.bias_ptr = (int32_t*)(w + L.off[i++]);
+    d.small_ws = (char*)(w + L.off[i++]);
     struct Guard { tasc_session* p; ~Guard() { if (p) tasc_session_destroy(p); } } guard{s};
     TASC_HIP(hipHostMalloc((void**)&s->host_counters, 32 * sizeof(u64), hipHostMallocDefault));
     const int n = batch * s->max_blocks;

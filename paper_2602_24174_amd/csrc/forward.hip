@@ -328,7 +328,12 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     a.n_strips = s->n_strips; a.max_new = s->max_new;
     a.row_tok = d.row_tok; a.n_rows = d.n_rows; a.pos0 = d.pos0; a.block_tab = d.block_tab; a.sel_rows = d.sel_rows;
     a.sel_tok = d.sel_tok; a.n_sel = n_sel;
-    a.x = d.x; a.q = (BF16*)d.q; a.att = (BF16*)d.att; a.act = (BF16*)d.act;
+    {
+        const TascSmallWs w = tasc_small_ws_layout(c);
+        a.x = (float*)(d.small_ws + w.x_off); a.x_stride = w.x_stride;
+        a.q = (BF16*)(d.small_ws + w.q_off); a.att = (BF16*)(d.small_ws + w.att_off); a.q_stride = w.q_stride;
+        a.act = (BF16*)(d.small_ws + w.act_off); a.act_stride = w.act_stride;
+    }
     a.part_val = d.part_val; a.part_idx = d.part_idx; a.amax = d.amax; a.logits_dbg = logits_dbg;
     a.k = tail ? tail->k : -1;
     a.drafts = tail ? tail->drafts : nullptr;

@@ -43,7 +43,7 @@ __device__ inline bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t 
 // points and would use FLAT instructions for it; a flat access counts against the LDS counter as well as
 // the vector-memory counter, so waiting for any LDS read would also wait for every weight load in flight.
 // Every pointer to device memory is therefore converted once to the global address space (gptr) and all
-// accesses go through typed global pointers (gld / gst and the ld_l2_* loads below).
+// accesses go through typed global pointers (gld / gst).
 #define GAS __attribute__((address_space(1)))
 template <class T>
 __device__ __forceinline__ GAS T* gptr(T* p) {
@@ -114,10 +114,16 @@ struct SmallArgs {
     const int32_t* sel_rows;
     const int32_t* sel_tok;
     int32_t n_sel;
-    float* x;
-    BF16* q;
-    BF16* att;
-    BF16* act;
+    // Activations handed from phase to phase.  Every buffer is written ONCE per launch, before anything reads it: the
+    // residual stream has a buffer per phase that updates it (x + i x_stride: i = 0 after the embedding, 2l + 1 after
+    // layer l's attention block, 2l + 2 after its MLP), q / the attention output / the MLP activation a buffer per
+    // layer.  A compute unit's L1 can therefore never hold a line from before the write (it is empty at launch), and
+    // the readers use ordinary 16-byte loads even when the producers' stores only went as far as the XCD's L2.
+    float* x;           // [2 L + 1][16][D]
+    BF16* q;            // [L][16][H hd]
+    BF16* att;          // [L][16][H hd]
+    BF16* act;          // [L][16][F]
+    size_t x_stride, q_stride, act_stride;     // elements
     float* part_val;
     int32_t* part_idx;
     int32_t* amax;
@@ -202,8 +208,8 @@ __device__ __noinline__ void grid_sync(GAS u64* counter, u64 target, GAS u32* er
 //   local = true   all members run on one XCD.  Its compute units share one L2 and their vector L1 caches
 //                  write through, so a store is visible to the group as soon as the L2 has acknowledged it:
 //                  every wave waits for its own stores, nobody writes the L2 back or invalidates anything.
-//                  The readers' half of the contract is ld_l2_*: data another member may have written in
-//                  this launch is only ever loaded past the L1.
+//                  The readers' half of the contract: no address is read before it has been written in this
+//                  launch (see SmallArgs), so no L1 holds a stale line.
 __device__ __noinline__ void group_sync(GAS u32* flags, int me, int n, u32 epoch, GAS u32* error, bool local) {
     if (local) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -236,25 +242,6 @@ __device__ inline u32 xcc_id() {
     return v & 15u;
 }
 
-// Loads of data that another workgroup wrote earlier in this launch: relaxed agent-scope atomic loads, which
-// the hardware serves from the L2 (never from the compute unit's L1, which may hold a line from before the
-// write).  With agent-scope barriers they are ordinary loads of a freshly invalidated cache.
-__device__ __forceinline__ u64 ld_l2_u64(const GAS void* p) {
-    return __hip_atomic_load((GAS u64*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ f32x4 ld_l2_f4(const GAS float* p) {
-    const u64 a = ld_l2_u64(p), b = ld_l2_u64(p + 2);
-    return f32x4{__uint_as_float((u32)a), __uint_as_float((u32)(a >> 32)), __uint_as_float((u32)b), __uint_as_float((u32)(b >> 32))};
-}
-__device__ __forceinline__ u32x2 ld_l2_u2(const GAS void* p) {
-    const u64 a = ld_l2_u64(p);
-    return u32x2{(u32)a, (u32)(a >> 32)};
-}
-__device__ __forceinline__ bf16x8 ld_l2_b8(const GAS BF16* p) {
-    const u64 a = ld_l2_u64(p), b = ld_l2_u64(p + 4);
-    return as_bf16x8((u32)a, (u32)(a >> 32), (u32)b, (u32)(b >> 32));
-}
-
 // ---------------------------------------------------------------- staging of the 16 activation rows
 // Wave w stages rows w and w + 8: s_act[r][0..D) = bf16(x[r] * g / sqrt(mean(x[r]^2) + eps)) for r < M, zero for
 // r >= M.  One pass: the row stays in registers between the sum of squares and the scaling.  D <= 256 NTC.
@@ -283,7 +270,7 @@ __device__ __forceinline__ void stage_normed_issue(const GAS float* x, const GAS
 #pragma unroll
         for (int t = 0; t < NTC; ++t) {
             const int c = 4 * (lane + 64 * t);
-            rg.v[j][t] = ld_l2_f4(xr + (c < D ? c : D - 4));        // unconditional, see load_w
+            rg.v[j][t] = gld<f32x4>(xr + (c < D ? c : D - 4));        // unconditional, see load_w
         }
     }
 #pragma unroll
@@ -341,7 +328,7 @@ __device__ __forceinline__ void stage_copy_issue(const GAS BF16* src, int M, int
     for (int u = 0; u < NC; ++u) {
         const int idx = min((int)threadIdx.x + u * SMALL_THREADS, total - 1);
         const int r = idx / per_row, k = (idx % per_row) * 8;
-        rg.v[u] = ld_l2_b8(src + (size_t)(r < M ? r : 0) * K + kc0 + k);
+        rg.v[u] = gld<bf16x8>(src + (size_t)(r < M ? r : 0) * K + kc0 + k);
     }
 }
 template <int NC>
@@ -446,12 +433,12 @@ __device__ __forceinline__ u32 phase_qkv(const SmallArgs& a, const SmallTabs& tb
     GAS BF16* kv_layer = gptr(a.kv_pool) + (size_t)layer * a.kv_layer_stride;
     const GAS float* rope_cos = gptr(a.rope_cos);
     const GAS float* rope_sin = gptr(a.rope_sin);
-    GAS BF16* q_out = gptr(a.q);
+    GAS BF16* q_out = gptr(a.q) + (size_t)layer * a.q_stride;
     const int nks = a.D / 32;
     const int m = lane & 15;
     u32 sink = 0;
     NormRegs<WKS> xr;                             // WKS = 3: D <= 768; WKS = 6: D <= 1536
-    stage_normed_issue<WKS>(gptr(a.x), gptr(L.g1), nullptr, a.M, a.D, xr);
+    stage_normed_issue<WKS>(gptr(a.x) + (size_t)(2 * layer) * a.x_stride, gptr(L.g1), nullptr, a.M, a.D, xr);
     __builtin_amdgcn_s_barrier();                 // every wave's activation loads are queued before any weight load
     bool staged = false;
     for (int base = wg; base < n_items; base += nwg * NI) {
@@ -533,10 +520,9 @@ __device__ __forceinline__ u32 phase_qkv(const SmallArgs& a, const SmallTabs& tb
 // ---------------------------------------------------------------- phases: projections with residual / SwiGLU
 // x[m][n] += sum_k src[m][k] W[n][k]    (output projection, down projection); item = 16 output features
 template <int NI, int WKS, class PF>
-__device__ __forceinline__ u32 phase_proj_resid(const SmallArgs& a, const GAS BF16* W, const GAS BF16* src, int N, int K, int wg, int nwg,
-                                                uint16_t* s_act, f32x4* s_red, PF prefetch) {
+__device__ __forceinline__ u32 phase_proj_resid(const SmallArgs& a, const GAS BF16* W, const GAS BF16* src, const GAS float* x_in,
+                                                GAS float* x_out, int N, int K, int wg, int nwg, uint16_t* s_act, f32x4* s_red, PF prefetch) {
     const int lane = threadIdx.x & 63, wave = wave_id();
-    GAS float* x = gptr(a.x);
     const int n_items = N / 16;
     const int m = lane & 15;
     u32 sink = 0;
@@ -550,7 +536,7 @@ __device__ __forceinline__ u32 phase_proj_resid(const SmallArgs& a, const GAS BF
         for (int j = 0; j < NI; ++j) wrow[j] = W + (size_t)min(base + j * nwg, n_items - 1) * (K / 32) * 512;
         const int my_item = base + wave * nwg;
         const bool mine = wave < NI && my_item < n_items && m < a.M;
-        GAS float* xp = x + (size_t)(mine ? m : 0) * N + (mine ? my_item : 0) * 16 + 4 * (lane >> 4);
+        const size_t xoff = (size_t)(mine ? m : 0) * N + (mine ? my_item : 0) * 16 + 4 * (lane >> 4);
         f32x4 xv = {0, 0, 0, 0};
         f32x4 acc[NI];
 #pragma unroll
@@ -559,7 +545,7 @@ __device__ __forceinline__ u32 phase_proj_resid(const SmallArgs& a, const GAS BF
             const int kw = min(SMALL_KC, K - kc0), nks = kw / 32;
             bf16x8 w[NI][WKS];
             load_w<NI, WKS>(wrow, kc0, nks, w);
-            if (kc0 == 0) xv = ld_l2_f4(xp);                 // unpredicated: lanes without an output read row 0
+            if (kc0 == 0) xv = gld<f32x4>(x_in + xoff);       // unpredicated: lanes without an output read row 0
             if (!staged) {
                 sink ^= prefetch();
                 stage_copy_finish<WKS>(cr, a.M, kw, s_act);
@@ -574,7 +560,7 @@ __device__ __forceinline__ u32 phase_proj_resid(const SmallArgs& a, const GAS BF
         put_partials<NI>(acc, s_red);
         if (mine) {
             xv += sum_tile(s_red, wave);
-            gst(xp, xv);
+            gst(x_out + xoff, xv);
         }
         __syncthreads();
     }
@@ -589,13 +575,13 @@ __device__ __forceinline__ u32 phase_gate_up(const SmallArgs& a, const SmallTabs
     const int lane = threadIdx.x & 63, wave = wave_id();
     const GAS BF16* Wgu = gptr((const BF16*)L.wgu_f);
     const size_t tile_row = (size_t)(a.D / 32) * 512;
-    GAS BF16* act = gptr(a.act);
+    GAS BF16* act = gptr(a.act) + (size_t)layer * a.act_stride;
     const int nks = a.D / 32;
     const int n_items = a.F / 16;
     const int m = lane & 15;
     u32 sink = 0;
     NormRegs<WKS> xr;
-    stage_normed_issue<WKS>(gptr(a.x), gptr(L.g2), nullptr, a.M, a.D, xr);
+    stage_normed_issue<WKS>(gptr(a.x) + (size_t)(2 * layer + 1) * a.x_stride, gptr(L.g2), nullptr, a.M, a.D, xr);
     __builtin_amdgcn_s_barrier();                 // every wave's activation loads are queued before any weight load
     bool staged = false;
     for (int base = wg; base < n_items; base += nwg * NI) {
@@ -647,8 +633,8 @@ __device__ __forceinline__ void phase_attn(const SmallArgs& a, const SmallTabs& 
     constexpr int TG = NKS <= 2 ? 3 : 1;
     const int Gq = a.H / a.Hkv;
     const GAS BF16* kv_layer = gptr(a.kv_pool) + (size_t)layer * a.kv_layer_stride;
-    const GAS BF16* q_in = gptr(a.q);
-    GAS BF16* att_out = gptr(a.att);
+    const GAS BF16* q_in = gptr(a.q) + (size_t)layer * a.q_stride;
+    GAS BF16* att_out = gptr(a.att) + (size_t)layer * a.q_stride;
     const size_t v_off = (size_t)a.Hkv * TASC_KV_BLOCK * hd;
     const int m = lane & 15, qd = lane >> 4;
     float* slot_o = s_buf;                                   // [wave][row][hd]
@@ -666,7 +652,7 @@ __device__ __forceinline__ void phase_attn(const SmallArgs& a, const SmallTabs& 
         bf16x8 qf[NKS];
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 v = ld_l2_b8(qp + 32 * ks + 8 * qd);
+            const bf16x8 v = gld<bf16x8>(qp + 32 * ks + 8 * qd);
             qf[ks] = okq ? v : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
         }
         float mx = -INFINITY, lsum = 0.f;
@@ -831,7 +817,7 @@ __device__ __forceinline__ void phase_lmhead(const SmallArgs& a, int wg, int nwg
         }
         if (!staged) {
             NormRegs<6> xr;
-            stage_normed_issue<6>(gptr(a.x), gptr(a.gf), gptr(a.sel_rows), a.n_sel, a.D, xr);
+            stage_normed_issue<6>(gptr(a.x) + (size_t)(2 * a.n_layers) * a.x_stride, gptr(a.gf), gptr(a.sel_rows), a.n_sel, a.D, xr);
             stage_normed_finish<6>(xr, a.n_sel, a.D, a.eps, s_act);
             staged = true;
         }
@@ -1064,17 +1050,17 @@ __device__ __forceinline__ u32 run_gate_up(const SmallArgs& a, const SmallTabs& 
     return phase_gate_up<1, WKS>(a, tb, layer, lw, lnw, s_act, s_red, pf);
 }
 template <class PF>
-__device__ __forceinline__ u32 run_proj(const SmallArgs& a, const GAS BF16* W, const GAS BF16* src, int N, int K, int lw, int lnw,
-                                        uint16_t* s_act, f32x4* s_red, PF pf) {
+__device__ __forceinline__ u32 run_proj(const SmallArgs& a, const GAS BF16* W, const GAS BF16* src, const GAS float* x_in, GAS float* x_out,
+                                        int N, int K, int lw, int lnw, uint16_t* s_act, f32x4* s_red, PF pf) {
     const int share = (N / 16 + lnw - 1) / lnw;
     if (K <= 768) {
-        if (share >= 3) return phase_proj_resid<3, 3>(a, W, src, N, K, lw, lnw, s_act, s_red, pf);
-        if (share == 2) return phase_proj_resid<2, 3>(a, W, src, N, K, lw, lnw, s_act, s_red, pf);
-        return phase_proj_resid<1, 3>(a, W, src, N, K, lw, lnw, s_act, s_red, pf);
+        if (share >= 3) return phase_proj_resid<3, 3>(a, W, src, x_in, x_out, N, K, lw, lnw, s_act, s_red, pf);
+        if (share == 2) return phase_proj_resid<2, 3>(a, W, src, x_in, x_out, N, K, lw, lnw, s_act, s_red, pf);
+        return phase_proj_resid<1, 3>(a, W, src, x_in, x_out, N, K, lw, lnw, s_act, s_red, pf);
     }
-    if (share >= 3) return phase_proj_resid<3, 6>(a, W, src, N, K, lw, lnw, s_act, s_red, pf);
-    if (share == 2) return phase_proj_resid<2, 6>(a, W, src, N, K, lw, lnw, s_act, s_red, pf);
-    return phase_proj_resid<1, 6>(a, W, src, N, K, lw, lnw, s_act, s_red, pf);
+    if (share >= 3) return phase_proj_resid<3, 6>(a, W, src, x_in, x_out, N, K, lw, lnw, s_act, s_red, pf);
+    if (share == 2) return phase_proj_resid<2, 6>(a, W, src, x_in, x_out, N, K, lw, lnw, s_act, s_red, pf);
+    return phase_proj_resid<1, 6>(a, W, src, x_in, x_out, N, K, lw, lnw, s_act, s_red, pf);
 }
 
 template <int NKS>
@@ -1182,8 +1168,12 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_small_step(SmallArgs a_in, in
                 else sink ^= run_gate_up<6>(a, tb, layer, lw, lnw, s_act, s_red, pf);
             } else {
                 const bool o_proj = sub == 2;
-                sink ^= run_proj(a, gptr((const BF16*)(o_proj ? L.wo_f : L.wd_f)), gptr((const BF16*)(o_proj ? a.att : a.act)), a.D,
-                                 o_proj ? a.H * a.hd : a.F, lw, lnw, s_act, s_red, pf);
+                // residual stream: read buffer 2l (+1 for the down projection), write the next one
+                const GAS float* x_in = gptr(a.x) + (size_t)(2 * layer + (o_proj ? 0 : 1)) * a.x_stride;
+                GAS float* x_out = gptr(a.x) + (size_t)(2 * layer + (o_proj ? 1 : 2)) * a.x_stride;
+                const GAS BF16* src = o_proj ? gptr(a.att) + (size_t)layer * a.q_stride : gptr(a.act) + (size_t)layer * a.act_stride;
+                sink ^= run_proj(a, gptr((const BF16*)(o_proj ? L.wo_f : L.wd_f)), src, x_in, x_out, a.D, o_proj ? a.H * a.hd : a.F, lw, lnw,
+                                 s_act, s_red, pf);
             }
         } else if (ph == n_lg_phases) {
             if (a.n_sel > 0) phase_lmhead(a, wg, nwg, s_act, s_best);

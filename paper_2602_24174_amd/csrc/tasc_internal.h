@@ -168,6 +168,7 @@ struct TascSessDev {
     int32_t* part_idx;   // [M_max, n_strips]
     int32_t* amax;       // [M_max] argmax token of every LM-head row
     float* att_part;     // attention split partials
+    char* small_ws;      // the small-batch kernel's per-phase / per-layer activation buffers (tasc_small_ws_bytes)
     int32_t* drafts;     // [B, TASC_MAX_K] used by tasc_generate
     int32_t* bias_ptr;   // [M_max, n_strips + 1] LM-head bias cursors of the small-batch kernel
 };
@@ -205,6 +206,29 @@ struct TascVerifyTail {
 };
 
 // library-wide options (tasc_config_set)
+// Layout of the small-batch kernel's activation buffers (each written once per launch): byte offsets, strides in
+// elements, and the total size in bytes.  16 rows throughout.
+struct TascSmallWs {
+    size_t x_off, x_stride;         // float [2 L + 1][16][D]
+    size_t q_off, att_off, q_stride;   // bf16 [L][16][H hd] each
+    size_t act_off, act_stride;     // bf16  [L][16][F]
+    size_t bytes;
+};
+inline TascSmallWs tasc_small_ws_layout(const tasc_model_desc& c) {
+    TascSmallWs w;
+    const size_t L = c.n_layers, HD = (size_t)c.n_heads * c.head_dim, al = 256;
+    auto up = [&](size_t v) { return (v + al - 1) / al * al; };
+    size_t o = 0;
+    w.x_off = o; w.x_stride = 16 * (size_t)c.d_model; o += up((2 * L + 1) * w.x_stride * 4);
+    w.q_stride = 16 * HD;
+    w.q_off = o; o += up(L * w.q_stride * 2);
+    w.att_off = o; o += up(L * w.q_stride * 2);
+    w.act_off = o; w.act_stride = 16 * (size_t)c.d_ffn; o += up(L * w.act_stride * 2);
+    w.bytes = o;
+    return w;
+}
+inline size_t tasc_small_ws_bytes(const tasc_model_desc& c) { return c.dtype == TASC_BF16 ? tasc_small_ws_layout(c).bytes : 256; }
+
 struct TascConfig {
     int small_path;           // 0: generic kernels only, 1: fused kernel one phase per launch, 2: persistent
     int small_grid;           // workgroups of the persistent kernel (0 = one per compute unit)
