@@ -208,7 +208,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         if (resid) k_splitk_reduce<true><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
         else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
     };
-    const int rows_pass = hd > 64 ? 16 : 32;
+    const int rows_pass = 32;
     const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
     {
         PROF(TASC_KC_PREPARE);

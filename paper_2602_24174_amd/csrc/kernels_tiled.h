@@ -139,22 +139,25 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     };
     // one pipeline step: fetch the weights of kt + 2 and the activations of kt + 1, multiply kt out of LDS, then
     // move kt + 1 (weights fetched a step earlier) into the other LDS buffer
+    // No load sits under a condition (a conditional load ends in a register copy at the join, which waits for the data
+    // and would serialise the prefetch): steps beyond the last re-read the last one and are never stored to LDS.
+    const int k_last = (nk - 1) * TG_BK;
     if (kt_begin < nk) {
         load_w(sw0, kt_begin * TG_BK);
         load_a(sa, kt_begin * TG_BK);
         store_wa(sw0, sa, 0);
-        if (kt_begin + 1 < nk) load_w(sw1, (kt_begin + 1) * TG_BK);
+        load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
     }
     __syncthreads();
     for (int kt = kt_begin; kt < nk; kt += 2) {
-        if (kt + 2 < nk) load_w(sw0, (kt + 2) * TG_BK);
-        if (kt + 1 < nk) load_a(sa, (kt + 1) * TG_BK);
+        load_w(sw0, min((kt + 2) * TG_BK, k_last));
+        load_a(sa, min((kt + 1) * TG_BK, k_last));
         multiply(0);
         if (kt + 1 < nk) {
             store_wa(sw1, sa, 1);          // buffer 1 was last read before the previous barrier
             __syncthreads();
-            if (kt + 3 < nk) load_w(sw1, (kt + 3) * TG_BK);
-            if (kt + 2 < nk) load_a(sa, (kt + 2) * TG_BK);
+            load_w(sw1, min((kt + 3) * TG_BK, k_last));
+            load_a(sa, min((kt + 2) * TG_BK, k_last));
             multiply(1);
             if (kt + 2 < nk) {
                 store_wa(sw0, sa, 0);
@@ -313,7 +316,7 @@ __global__ void k_bias_ptr(BiasCsr bias, const int32_t* __restrict__ sel_tok, in
 }
 
 // ---------------------------------------------------------------- paged GQA attention, any number of rows
-// One workgroup per (sequence, KV head, pass of 32 query rows (16 when head_dim = 128)); the scheme is the
+// One workgroup per (sequence, KV head, pass of 32 query rows); the scheme is the
 // attention phase of the small-batch kernel (S^T = K Q^T, O^T = V^T P^T, key tiles of 32 at absolute
 // positions dealt to the 8 waves, fixed merge tree), with plain kernel arguments.
 struct AttnArgs {
@@ -329,12 +332,12 @@ struct AttnArgs {
 };
 
 template <int NKS>
-#define TILED_ATT_SLOT 2048           // floats of one attention combine slot (rows of a pass x head_dim)
+#define TILED_ATT_SLOT 2048           // floats of one attention combine slot (32 rows x head_dim 64, or 16 rows x 128)
 __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) float s_buf[4 * TILED_ATT_SLOT + 4 * 32 * 2];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr int hd = 32 * NKS, ndt = 2 * NKS;
-    constexpr int RT = NKS <= 2 ? 2 : 1, rows_pass = 16 * RT;
+    constexpr int RT = 2, rows_pass = 16 * RT;
     const int Gq = a.H / a.Hkv;
     const int R = a.nq * Gq;
     const size_t v_off = (size_t)a.Hkv * TASC_KV_BLOCK * hd;
@@ -373,24 +376,29 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
 #pragma unroll
         for (int dt = 0; dt < ndt; ++dt) o[rt][dt] = f32x4{0, 0, 0, 0};
     }
-    for (int t = wave; t < n_tiles; t += SMALL_NW) {
-        const int key0 = t * 32;
+    // The wave's tiles (t = wave, wave + 8, ..) alternate between two register sets (head_dim <= 64): while one tile is
+    // multiplied, the next one's keys and values are already on their way.  Loads are unconditional: a tile past the end
+    // re-reads the last one (never multiplied), a second page beyond the sequence re-reads the first (its keys are
+    // masked and the pool holds no NaN patterns).
+    struct KV { bf16x8 kf0[NKS], kf1[NKS], vf[ndt]; };
+    auto load_tile = [&](KV& kv, int t) __attribute__((always_inline)) {
+        const int key0 = min(t, n_tiles - 1) * 32;
         const BF16* pg0 = a.kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK] * a.page_elems;
-        const bool has1 = key0 + 16 < L;
-        const BF16* pg1 = has1 ? a.kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK + 1] * a.page_elems : pg0;
-        bf16x8 kf0[NKS], kf1[NKS], vf[ndt];
+        const BF16* pg1 = a.kv_layer + (size_t)bt[key0 / TASC_KV_BLOCK + (key0 + 16 < L ? 1 : 0)] * a.page_elems;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            kf0[ks] = *reinterpret_cast<const bf16x8*>(pg0 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
-            kf1[ks] = *reinterpret_cast<const bf16x8*>(pg1 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
+            kv.kf0[ks] = *reinterpret_cast<const bf16x8*>(pg0 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
+            kv.kf1[ks] = *reinterpret_cast<const bf16x8*>(pg1 + (size_t)(g * TASC_KV_BLOCK + m) * hd + 32 * ks + 8 * qd);
         }
 #pragma unroll
         for (int dt = 0; dt < ndt; ++dt) {
-            const uint2 h0 = *reinterpret_cast<const uint2*>(pg0 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd);
-            const uint2 h1 = has1 ? *reinterpret_cast<const uint2*>(pg1 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd)
-                                  : make_uint2(0, 0);
-            vf[dt] = as_bf16x8(h0.x, h0.y, h1.x, h1.y);
+            const u32x2 h0 = *reinterpret_cast<const u32x2*>(pg0 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd);
+            const u32x2 h1 = *reinterpret_cast<const u32x2*>(pg1 + v_off + (size_t)(g * hd + 16 * dt + m) * TASC_KV_BLOCK + 4 * qd);
+            kv.vf[dt] = as_bf16x8(h0[0], h0[1], h1[0], h1[1]);
         }
+    };
+    auto multiply_tile = [&](const KV& kv, int t) __attribute__((always_inline)) {
+        const int key0 = t * 32;
         f32x4 s0[RT], s1[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) { s0[rt] = f32x4{0, 0, 0, 0}; s1[rt] = f32x4{0, 0, 0, 0}; }
@@ -398,8 +406,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
         for (int ks = 0; ks < NKS; ++ks) {
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
-                s0[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf0[ks], qf[rt][ks], s0[rt], 0, 0, 0);
-                s1[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf1[ks], qf[rt][ks], s1[rt], 0, 0, 0);
+                s0[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kv.kf0[ks], qf[rt][ks], s0[rt], 0, 0, 0);
+                s1[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kv.kf1[ks], qf[rt][ks], s1[rt], 0, 0, 0);
             }
         }
 #pragma unroll
@@ -435,30 +443,54 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
 #pragma unroll
             for (int dt = 0; dt < ndt; ++dt) {
                 o[rt][dt] *= corr;
-                o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pk, o[rt][dt], 0, 0, 0);
+                o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kv.vf[dt], pk, o[rt][dt], 0, 0, 0);
             }
         }
+    };
+    if constexpr (NKS <= 2) {
+        if (wave < n_tiles) {
+            KV kva, kvb;
+            load_tile(kva, wave);
+            for (int t = wave; t < n_tiles; t += 2 * SMALL_NW) {
+                load_tile(kvb, t + SMALL_NW);
+                multiply_tile(kva, t);
+                load_tile(kva, t + 2 * SMALL_NW);
+                if (t + SMALL_NW < n_tiles) multiply_tile(kvb, t + SMALL_NW);
+            }
+        }
+    } else {
+        // head_dim 128: one register set (two row tiles of accumulators take the room of the second)
+        for (int t = wave; t < n_tiles; t += SMALL_NW) {
+            KV kv;
+            load_tile(kv, t);
+            multiply_tile(kv, t);
+        }
     }
-    auto merge_round = [&](bool writer, bool reader, int sl) {
+    // fixed merge tree ((0+1)+(2+3))+((4+5)+(6+7)) through four LDS slots; a slot holds MRT row tiles, so head_dim 128
+    // runs the tree once per row tile
+    constexpr int MRT = NKS == 4 ? 1 : RT;
+    auto merge_round = [&](bool writer, bool reader, int sl, int rt0) {
         float* so = s_buf + sl * TILED_ATT_SLOT;
         if (writer) {
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
+            for (int q = 0; q < MRT; ++q) {
+                const int rt = rt0 + q;
 #pragma unroll
                 for (int dt = 0; dt < ndt; ++dt)
-                    *reinterpret_cast<f32x4*>(so + (size_t)(16 * rt + m) * hd + 16 * dt + 4 * qd) = o[rt][dt];
+                    *reinterpret_cast<f32x4*>(so + (size_t)(16 * q + m) * hd + 16 * dt + 4 * qd) = o[rt][dt];
                 if (qd == 0) {
-                    slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 0] = mx[rt];
-                    slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 1] = lsum[rt];
+                    slot_ml[(sl * rows_pass + 16 * q + m) * 2 + 0] = mx[rt];
+                    slot_ml[(sl * rows_pass + 16 * q + m) * 2 + 1] = lsum[rt];
                 }
             }
         }
         __syncthreads();
         if (reader) {
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                const float m2 = slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 0];
-                const float l2 = slot_ml[(sl * rows_pass + 16 * rt + m) * 2 + 1];
+            for (int q = 0; q < MRT; ++q) {
+                const int rt = rt0 + q;
+                const float m2 = slot_ml[(sl * rows_pass + 16 * q + m) * 2 + 0];
+                const float l2 = slot_ml[(sl * rows_pass + 16 * q + m) * 2 + 1];
                 const float mn = fmaxf(mx[rt], m2);
                 const float c1 = mn == -INFINITY ? 1.f : __expf(mx[rt] - mn);
                 const float c2 = mn == -INFINITY ? 1.f : __expf(m2 - mn);
@@ -466,15 +498,17 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
                 mx[rt] = mn;
 #pragma unroll
                 for (int dt = 0; dt < ndt; ++dt) {
-                    const f32x4 o2 = *reinterpret_cast<const f32x4*>(so + (size_t)(16 * rt + m) * hd + 16 * dt + 4 * qd);
+                    const f32x4 o2 = *reinterpret_cast<const f32x4*>(so + (size_t)(16 * q + m) * hd + 16 * dt + 4 * qd);
                     o[rt][dt] = o[rt][dt] * c1 + o2 * c2;
                 }
             }
         }
         __syncthreads();
     };
-    for (int stride = 1; stride < SMALL_NW; stride <<= 1)
-        merge_round((wave & (2 * stride - 1)) == stride, (wave & (2 * stride - 1)) == 0, (wave / (2 * stride)) & 3);
+#pragma unroll
+    for (int rt0 = 0; rt0 < RT; rt0 += MRT)
+        for (int stride = 1; stride < SMALL_NW; stride <<= 1)
+            merge_round((wave & (2 * stride - 1)) == stride, (wave & (2 * stride - 1)) == 0, (wave / (2 * stride)) & 3, rt0);
     if (wave == 0) {
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
