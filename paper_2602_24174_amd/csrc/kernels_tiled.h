@@ -40,7 +40,7 @@ __device__ inline int tile_row(int i, int lane) { return 8 * (i >> 2) + 4 * (lan
 // BN x BM = output features x rows of the workgroup tile; WN x WM waves, each computing a
 // (BN / WN) x (BM / WM) block as TI x TJ MFMA tiles of 32 x 32.
 template <int EPI, int BN, int BM, int WN, int WM>
-__global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_gemm_tiled(const BF16* __restrict__ A, const BF16* __restrict__ W, int M, int N,
+__global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1, WN * WM >= 8 ? 2 : 1))) void k_gemm_tiled(const BF16* __restrict__ A, const BF16* __restrict__ W, int M, int N,
                                                              int K, float* __restrict__ outf, BF16* __restrict__ outb, LmEpi lm) {
     constexpr int THREADS = 64 * WN * WM;
     constexpr int SN = BN / WN, SM = BM / WM;          // the wave's span in n and m
@@ -65,46 +65,35 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     // two register sets (0 and 1, separate arrays so that both stay in registers): while step kt is multiplied out
     // of LDS, step kt + 1 waits in one set and step kt + 2 is being fetched into the other, so a global load has two
     // steps' worth of time to arrive
-    static_assert(PW == 4 && PA == 4, "staging code below is written out for four passes per operand");
-    // (native vector types: a struct-typed uint4 would be copied through private memory)
-    struct StageW { u32x4 w0, w1, w2, w3; } sw0, sw1;   // weights: fetched two steps ahead (HBM latency)
-    struct StageA { u32x4 a0, a1, a2, a3; } sa;         // activations: one step ahead (they sit in L2)
+    // (native vector types in plain arrays with compile-time indices: a struct-typed uint4 would be copied through
+    // private memory)
+    struct StageW { u32x4 w[PW]; } sw0, sw1;   // weights: fetched two steps ahead (HBM latency)
+    struct StageA { u32x4 a[PA]; } sa;         // activations: one step ahead (they sit in L2)
     // rows past the matrix are read from its last row (unconditional loads keep the memory pipeline's wait counts
     // exact); what they produce is never stored
     const int wrow_last = N - 1 - n0 - ld_row, arow_last = M - 1 - m0 - ld_row;   // clamp bounds relative to the thread's first row
     const BF16* wbase = W + (size_t)(n0 + ld_row) * K + ld_col;
     const BF16* abase = A + (size_t)(m0 + ld_row) * K + ld_col;
-    const BF16* wp0 = wbase + (ptrdiff_t)min(0 * ROWS_PASS, wrow_last) * K;
-    const BF16* wp1 = wbase + (ptrdiff_t)min(1 * ROWS_PASS, wrow_last) * K;
-    const BF16* wp2 = wbase + (ptrdiff_t)min(2 * ROWS_PASS, wrow_last) * K;
-    const BF16* wp3 = wbase + (ptrdiff_t)min(3 * ROWS_PASS, wrow_last) * K;
-    const BF16* ap0 = abase + (ptrdiff_t)min(0 * ROWS_PASS, arow_last) * K;
-    const BF16* ap1 = abase + (ptrdiff_t)min(1 * ROWS_PASS, arow_last) * K;
-    const BF16* ap2 = abase + (ptrdiff_t)min(2 * ROWS_PASS, arow_last) * K;
-    const BF16* ap3 = abase + (ptrdiff_t)min(3 * ROWS_PASS, arow_last) * K;
+    int woff[PW], aoff[PA];                     // element offsets of the thread's rows (a tile spans < 2^31 elements)
+#pragma unroll
+    for (int p = 0; p < PW; ++p) woff[p] = min(p * ROWS_PASS, wrow_last) * K;
+#pragma unroll
+    for (int p = 0; p < PA; ++p) aoff[p] = min(p * ROWS_PASS, arow_last) * K;
     auto load_w = [&](StageW& s, int k0) __attribute__((always_inline)) {
-        s.w0 = *reinterpret_cast<const u32x4*>(wp0 + k0);
-        s.w1 = *reinterpret_cast<const u32x4*>(wp1 + k0);
-        s.w2 = *reinterpret_cast<const u32x4*>(wp2 + k0);
-        s.w3 = *reinterpret_cast<const u32x4*>(wp3 + k0);
+#pragma unroll
+        for (int p = 0; p < PW; ++p) s.w[p] = *reinterpret_cast<const u32x4*>(wbase + woff[p] + k0);
     };
     auto load_a = [&](StageA& s, int k0) __attribute__((always_inline)) {
-        s.a0 = *reinterpret_cast<const u32x4*>(ap0 + k0);
-        s.a1 = *reinterpret_cast<const u32x4*>(ap1 + k0);
-        s.a2 = *reinterpret_cast<const u32x4*>(ap2 + k0);
-        s.a3 = *reinterpret_cast<const u32x4*>(ap3 + k0);
+#pragma unroll
+        for (int p = 0; p < PA; ++p) s.a[p] = *reinterpret_cast<const u32x4*>(abase + aoff[p] + k0);
     };
     auto store_wa = [&](const StageW& w, const StageA& a, int buf) __attribute__((always_inline)) {
         uint16_t* dw = sW + (size_t)(buf * BN + ld_row) * TG_LD + ld_col;
         uint16_t* da = sA + (size_t)(buf * BM + ld_row) * TG_LD + ld_col;
-        *reinterpret_cast<u32x4*>(dw + (size_t)0 * ROWS_PASS * TG_LD) = w.w0;
-        *reinterpret_cast<u32x4*>(dw + (size_t)1 * ROWS_PASS * TG_LD) = w.w1;
-        *reinterpret_cast<u32x4*>(dw + (size_t)2 * ROWS_PASS * TG_LD) = w.w2;
-        *reinterpret_cast<u32x4*>(dw + (size_t)3 * ROWS_PASS * TG_LD) = w.w3;
-        *reinterpret_cast<u32x4*>(da + (size_t)0 * ROWS_PASS * TG_LD) = a.a0;
-        *reinterpret_cast<u32x4*>(da + (size_t)1 * ROWS_PASS * TG_LD) = a.a1;
-        *reinterpret_cast<u32x4*>(da + (size_t)2 * ROWS_PASS * TG_LD) = a.a2;
-        *reinterpret_cast<u32x4*>(da + (size_t)3 * ROWS_PASS * TG_LD) = a.a3;
+#pragma unroll
+        for (int p = 0; p < PW; ++p) *reinterpret_cast<u32x4*>(dw + (size_t)p * ROWS_PASS * TG_LD) = w.w[p];
+#pragma unroll
+        for (int p = 0; p < PA; ++p) *reinterpret_cast<u32x4*>(da + (size_t)p * ROWS_PASS * TG_LD) = a.a[p];
     };
     f32x16 acc[TI][TJ];
 #pragma unroll
@@ -142,25 +131,47 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     // No load sits under a condition (a conditional load ends in a register copy at the join, which waits for the data
     // and would serialise the prefetch): steps beyond the last re-read the last one and are never stored to LDS.
     const int k_last = (nk - 1) * TG_BK;
-    if (kt_begin < nk) {
-        load_w(sw0, kt_begin * TG_BK);
-        load_a(sa, kt_begin * TG_BK);
-        store_wa(sw0, sa, 0);
-        load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
-    }
-    __syncthreads();
-    for (int kt = kt_begin; kt < nk; kt += 2) {
-        load_w(sw0, min((kt + 2) * TG_BK, k_last));
-        load_a(sa, min((kt + 1) * TG_BK, k_last));
-        multiply(0);
-        if (kt + 1 < nk) {
-            store_wa(sw1, sa, 1);          // buffer 1 was last read before the previous barrier
-            __syncthreads();
-            load_w(sw1, min((kt + 3) * TG_BK, k_last));
-            load_a(sa, min((kt + 2) * TG_BK, k_last));
-            multiply(1);
-            if (kt + 2 < nk) {
-                store_wa(sw0, sa, 0);
+    constexpr bool DEEP = PW <= 4;              // the 4-wave 256 x 256 tile has no registers for a second weight set
+    if constexpr (DEEP) {
+        if (kt_begin < nk) {
+            load_w(sw0, kt_begin * TG_BK);
+            load_a(sa, kt_begin * TG_BK);
+            store_wa(sw0, sa, 0);
+            load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
+        }
+        __syncthreads();
+        for (int kt = kt_begin; kt < nk; kt += 2) {
+            load_w(sw0, min((kt + 2) * TG_BK, k_last));
+            load_a(sa, min((kt + 1) * TG_BK, k_last));
+            multiply(0);
+            if (kt + 1 < nk) {
+                store_wa(sw1, sa, 1);          // buffer 1 was last read before the previous barrier
+                __syncthreads();
+                load_w(sw1, min((kt + 3) * TG_BK, k_last));
+                load_a(sa, min((kt + 2) * TG_BK, k_last));
+                multiply(1);
+                if (kt + 2 < nk) {
+                    store_wa(sw0, sa, 0);
+                    __syncthreads();
+                }
+            }
+        }
+    } else {
+        // one step ahead for both operands: fetch kt + 1 into registers, multiply kt out of one LDS buffer, then park
+        // kt + 1 in the other (last read before the previous barrier)
+        if (kt_begin < nk) {
+            load_w(sw0, kt_begin * TG_BK);
+            load_a(sa, kt_begin * TG_BK);
+            store_wa(sw0, sa, 0);
+        }
+        __syncthreads();
+        for (int kt = kt_begin; kt < nk; ++kt) {
+            const int buf = (kt - kt_begin) & 1;
+            load_w(sw0, min((kt + 1) * TG_BK, k_last));
+            load_a(sa, min((kt + 1) * TG_BK, k_last));
+            if (buf == 0) multiply(0); else multiply(1);
+            if (kt + 1 < nk) {
+                store_wa(sw0, sa, buf ^ 1);
                 __syncthreads();
             }
         }
