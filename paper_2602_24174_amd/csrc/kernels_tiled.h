@@ -13,6 +13,9 @@
 #include "kernels_small.h"
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+#ifndef IGLP
+#define IGLP 0
+#endif
 
 #define TG_BK 64
 #define TG_LD (TG_BK + 8)                                     // padded LDS row (elements)
@@ -111,6 +114,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
         outf += (size_t)blockIdx.y * M * N;
     }
     auto multiply = [&](int buf) __attribute__((always_inline)) {
+        __builtin_amdgcn_iglp_opt(IGLP);
         const uint16_t* bw = sW + (size_t)(buf * BN + wn * SN + (lane & 31)) * TG_LD + 8 * (lane >> 5);
         const uint16_t* ba = sA + (size_t)(buf * BM + wm * SM + (lane & 31)) * TG_LD + 8 * (lane >> 5);
 #pragma unroll
