@@ -144,21 +144,24 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
             load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
         }
         __syncthreads();
+        // The body is free of branches around loads and LDS stores: a value loaded before a multiply but only used
+        // under a condition would be sunk into the conditional block, behind the multiply it was meant to overlap.
+        // Steps past the last one re-read the last one; their LDS tiles are written but never multiplied.
         for (int kt = kt_begin; kt < nk; kt += 2) {
-            load_w(sw0, min((kt + 2) * TG_BK, k_last));
-            load_a(sa, min((kt + 1) * TG_BK, k_last));
+            load_a(sa, min((kt + 1) * TG_BK, k_last));     // activations first: loads return in order, and these are needed
+            load_w(sw0, min((kt + 2) * TG_BK, k_last));     // a step earlier than the weights issued with them
+            __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of the multiply
             multiply(0);
-            if (kt + 1 < nk) {
-                store_wa(sw1, sa, 1);          // buffer 1 was last read before the previous barrier
-                __syncthreads();
-                load_w(sw1, min((kt + 3) * TG_BK, k_last));
-                load_a(sa, min((kt + 2) * TG_BK, k_last));
-                multiply(1);
-                if (kt + 2 < nk) {
-                    store_wa(sw0, sa, 0);
-                    __syncthreads();
-                }
-            }
+            __builtin_amdgcn_sched_barrier(0);
+            store_wa(sw1, sa, 1);                           // buffer 1 was last read before the previous barrier
+            __syncthreads();
+            load_a(sa, min((kt + 2) * TG_BK, k_last));
+            load_w(sw1, min((kt + 3) * TG_BK, k_last));
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 1 < nk) multiply(1);
+            __builtin_amdgcn_sched_barrier(0);
+            store_wa(sw0, sa, 0);
+            __syncthreads();
         }
     } else {
         // one step ahead for both operands: fetch kt + 1 into registers, multiply kt out of one LDS buffer, then park
@@ -171,13 +174,13 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
         __syncthreads();
         for (int kt = kt_begin; kt < nk; ++kt) {
             const int buf = (kt - kt_begin) & 1;
-            load_w(sw0, min((kt + 1) * TG_BK, k_last));
             load_a(sa, min((kt + 1) * TG_BK, k_last));
+            load_w(sw0, min((kt + 1) * TG_BK, k_last));
+            __builtin_amdgcn_sched_barrier(0);
             if (buf == 0) multiply(0); else multiply(1);
-            if (kt + 1 < nk) {
-                store_wa(sw0, sa, buf ^ 1);
-                __syncthreads();
-            }
+            __builtin_amdgcn_sched_barrier(0);
+            store_wa(sw0, sa, buf ^ 1);
+            __syncthreads();
         }
     }
 
