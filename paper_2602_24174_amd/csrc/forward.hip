@@ -161,7 +161,10 @@ tasc_status tiled_attrs() {
 template <int EPI>
 void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf, BF16* outb, const LmEpi& lm, int slices,
                  hipStream_t st) {
-    if (M >= kLargeTileRows) {
+    // large tiles need enough of them to fill the chip: narrow outputs stay on the small tile (the k order, and so
+    // every row's result, is the same for both shapes)
+    const long large_wgs = (long)((M + 255) / 256) * ((N + 255) / 256) * slices;
+    if (M >= kLargeTileRows && large_wgs >= 128) {
         dim3 g((unsigned)(((M + 255) / 256) * ((N + 255) / 256)), (unsigned)slices);
         k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
     } else {
@@ -190,8 +193,13 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
     // narrow outputs (few column tiles) are computed in k-slices; the slice count depends on N and K only
     auto slices = [&](int N, int K) {
         const int n_nt = (N + 127) / 128, nk = K / TG_BK;
-        if (n_nt >= 64) return 1;
-        int ks = nk < TG_MAX_SLICES ? nk : TG_MAX_SLICES;
+        if (n_nt >= 32) return 1;
+        // few column tiles: one slice per 12 k-steps, or enough for about 24 (column tile, slice) pairs if that is
+        // more, but slices of at least 4 k-steps and no more slices than needed: each costs a pass over the fp32
+        // partial sums (measured on the qkv / output / down projections of the 0.5B and 1.5B shapes)
+        int ks = nk / 12 > (24 + n_nt - 1) / n_nt ? nk / 12 : (24 + n_nt - 1) / n_nt;
+        ks = ks < nk / 4 ? ks : nk / 4;
+        ks = ks < TG_MAX_SLICES ? ks : TG_MAX_SLICES;
         return ks < 1 ? 1 : ks;
     };
     // out (+)= A W^T through k-slices and the ordered reduction

@@ -137,30 +137,35 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     const int k_last = (nk - 1) * TG_BK;
     constexpr bool DEEP = PW <= 4;              // the 4-wave 256 x 256 tile has no registers for a second weight set
     if constexpr (DEEP) {
+        // Step kt multiplies LDS buffer kt % 2.  At its start the tile of step kt + 1 (activations fetched a step ago,
+        // weights two steps ago) is parked in the other buffer, which nobody has read since the last barrier, and the
+        // next fetches are issued; the LDS stores and the fetches then run under the step's MFMAs.
+        // The body is free of branches around loads and LDS stores: a value loaded before a multiply but only used
+        // under a condition would be sunk into the conditional block, behind the multiply it was meant to overlap.
+        // Steps past the last one re-read the last one; their LDS tiles are written but never multiplied.
         if (kt_begin < nk) {
             load_w(sw0, kt_begin * TG_BK);
             load_a(sa, kt_begin * TG_BK);
             store_wa(sw0, sa, 0);
+            load_a(sa, min((kt_begin + 1) * TG_BK, k_last));
             load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
+            load_w(sw0, min((kt_begin + 2) * TG_BK, k_last));
         }
         __syncthreads();
-        // The body is free of branches around loads and LDS stores: a value loaded before a multiply but only used
-        // under a condition would be sunk into the conditional block, behind the multiply it was meant to overlap.
-        // Steps past the last one re-read the last one; their LDS tiles are written but never multiplied.
         for (int kt = kt_begin; kt < nk; kt += 2) {
-            load_a(sa, min((kt + 1) * TG_BK, k_last));     // activations first: loads return in order, and these are needed
-            load_w(sw0, min((kt + 2) * TG_BK, k_last));     // a step earlier than the weights issued with them
-            __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of the multiply
+            store_wa(sw1, sa, 1);                           // step kt + 1
+            load_a(sa, min((kt + 2) * TG_BK, k_last));      // activations first: loads return in order
+            load_w(sw1, min((kt + 3) * TG_BK, k_last));
+            __builtin_amdgcn_sched_barrier(0);              // stores and fetches stay ahead of the multiply
             multiply(0);
             __builtin_amdgcn_sched_barrier(0);
-            store_wa(sw1, sa, 1);                           // buffer 1 was last read before the previous barrier
             __syncthreads();
-            load_a(sa, min((kt + 2) * TG_BK, k_last));
-            load_w(sw1, min((kt + 3) * TG_BK, k_last));
+            store_wa(sw0, sa, 0);                           // step kt + 2
+            load_a(sa, min((kt + 3) * TG_BK, k_last));
+            load_w(sw0, min((kt + 4) * TG_BK, k_last));
             __builtin_amdgcn_sched_barrier(0);
             if (kt + 1 < nk) multiply(1);
             __builtin_amdgcn_sched_barrier(0);
-            store_wa(sw0, sa, 0);
             __syncthreads();
         }
     } else {
