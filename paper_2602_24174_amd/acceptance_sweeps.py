@@ -1,0 +1,157 @@
+"""Acceptance instrumentation of TASC-spec on the synthetic workloads: per-position acceptance and the
+lambda / k / p_min / drafter-source / bias-strength sweeps (paper, Results, "TASC-spec": acceptance rate against
+draft position; Appendix, mixture-weight ablation; the drafter comparison table).
+
+    python -m paper_2602_24174_amd.acceptance_sweeps [--config cfg2] [--docs N] [--gen G] [--sweeps lambda,k,...]
+
+Every point is one tasc_generate call on the GPU (tables rebuilt where p_min changes, the model rebuilt where the
+LM-head bias strength changes); nothing here computes a step of the method, it only varies the parameters and
+turns the accept-length histogram that tasc_generate returns into rates:
+
+  rate(i)  = share of (verify step, sequence) pairs that accepted at least i drafts        (i = 1..k)
+  cond(i)  = rate(i) / rate(i - 1): acceptance of draft position i given that i - 1 was reached
+
+The source sweep uses the mixture's end points: lambda = 1 is the corpus tables alone, lambda = 0 the context
+statistics alone.  The bias sweep lowers alpha of the corpus-biased LM head, which makes the target less
+predictable from the corpus (alpha = 0: the target ignores the corpus, accept lengths fall to about 0 and a verify
+step emits one token: the worst case for the verify path).  A greedy target tends to fall into a cycle, which the
+context statistics then predict whatever the corpus says, so the bias sweep also prints every point with the corpus
+tables alone: that line shows the verify path when few drafts are accepted.
+"""
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def position_rates(accept_hist, k):
+    """accept_hist[m] = number of (step, sequence) pairs with accept length m.  Returns (rate[1..k], cond[1..k])."""
+    total = sum(accept_hist[:k + 1])
+    if total == 0:
+        return [0.0] * k, [0.0] * k
+    reach = [0] * (k + 2)
+    for m in range(k, -1, -1):
+        reach[m] = reach[m + 1] + accept_hist[m]      # pairs with accept length >= m
+    rate = [reach[i] / total for i in range(1, k + 1)]
+    cond = [reach[i] / reach[i - 1] if reach[i - 1] else 0.0 for i in range(1, k + 1)]
+    return rate, cond
+
+
+class SweepRig:
+    """One workload on the GPU; run(...) = one tasc_generate with the given drafting parameters."""
+
+    def __init__(self, cfg, max_rows=None):
+        import torch
+        import workload as W
+        import paper_2602_24174_amd as T
+        self.T, self.W, self.torch, self.cfg = T, W, torch, cfg
+        self.corpus = W.make_corpus(cfg)
+        self.d_corpus = torch.from_numpy(self.corpus[0]).cuda()
+        self.prompts, self.poff = W.make_prompts(cfg)
+        self.d_prompts = torch.from_numpy(self.prompts).cuda()
+        from paper_2602_24174_amd.binding import TASC_MAX_K
+        self.max_rows = max_rows or max(TASC_MAX_K + 1, 16 if cfg.batch == 1 else 64)
+        self.max_len = cfg.prompt_len + cfg.gen_len + 2 * self.max_rows
+        self.out = torch.zeros((cfg.batch, cfg.gen_len), dtype=torch.int32, device="cuda")
+        self.tables = {}
+        self.set_bias(cfg.bias_alpha)
+
+    def set_bias(self, alpha):
+        """(Re)build the target with LM-head bias strength alpha; the layer weights do not depend on it."""
+        T, W = self.T, self.W
+        cfg = self.cfg.scaled(bias_alpha=alpha)
+        if not hasattr(self, "weights"):
+            self.weights = W.make_model(cfg, self.corpus)
+        else:
+            self.session.close()
+            self.model.close()
+            self.weights["bias"] = W.bigram_bias_csr(self.corpus[0], self.corpus[1], cfg.vocab, alpha) if alpha != 0 else None
+        self.model = T.tasc_model_create(cfg, self.weights, self.max_len)
+        self.session = T.tasc_session_create(self.model, cfg.batch, self.max_len, self.max_rows)
+        g = T.tasc_generate(self.model, None, self.session, self.d_prompts, self.poff, cfg.gen_len, T.spec_params(0), self.out, None, 0)
+        self.greedy_tokens = self.out.cpu().numpy().copy()
+        self.greedy_tps = g.emitted / (g.decode_ms / 1e3)
+
+    def table(self, p_min):
+        if p_min not in self.tables:
+            c = self.cfg
+            self.tables[p_min] = self.T.tasc_ngram_build(self.d_corpus, self.corpus[1], c.vocab, c.n_max, p_min)
+        return self.tables[p_min]
+
+    def run(self, k=None, lam=None, p_min=None, p_min_ctx=None):
+        c, T = self.cfg, self.T
+        k = c.k if k is None else k
+        lam = c.lam if lam is None else lam
+        p_min = c.p_min if p_min is None else p_min
+        params = T.spec_params(k, int(round(lam * 65536)), c.p_min_ctx if p_min_ctx is None else p_min_ctx, 1)
+        T.tasc_generate(self.model, self.table(p_min), self.session, self.d_prompts, self.poff, c.gen_len, params, self.out, None, 0)  # warm
+        st = T.tasc_generate(self.model, self.table(p_min), self.session, self.d_prompts, self.poff, c.gen_len, params, self.out, None, 0)
+        same = bool((self.out.cpu().numpy() == self.greedy_tokens).all())
+        hist = list(st.accept_hist[:k + 1])
+        rate, cond = position_rates(hist, k)
+        pairs = max(1, sum(hist))
+        return {"k": k, "lambda": lam, "p_min": p_min, "steps": st.steps, "mean_accept": st.accepted / pairs, "hist": hist,
+                "rate": rate, "cond": cond, "tokens_per_s": st.emitted / (st.decode_ms / 1e3),
+                "speedup": st.emitted / (st.decode_ms / 1e3) / self.greedy_tps, "equals_greedy": same}
+
+
+def fmt(label, r):
+    rates = " ".join(f"{x:.2f}" for x in r["rate"])
+    return (f"  {label:<22s} steps {r['steps']:4d}  mean accept {r['mean_accept']:5.2f} of {r['k']:2d}  tokens/s {r['tokens_per_s']:9.0f}"
+            f"  x{r['speedup']:.2f} vs greedy  {'==' if r['equals_greedy'] else '!='} greedy  rate(i): {rates}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--docs", type=int, default=0, help="corpus size override (0 = the configuration's)")
+    ap.add_argument("--gen", type=int, default=0, help="tokens to generate (0 = the configuration's)")
+    ap.add_argument("--sweeps", default="position,lambda,k,p_min,source,bias")
+    args = ap.parse_args()
+    import workload as W
+    cfg = W.get_config(args.config)
+    if args.docs:
+        cfg = cfg.scaled(n_docs=args.docs)
+    if args.gen:
+        cfg = cfg.scaled(gen_len=args.gen)
+    rig = SweepRig(cfg)
+    which = args.sweeps.split(",")
+    print(f"{cfg.name}: batch {cfg.batch}, prompt {cfg.prompt_len}, generate {cfg.gen_len}, corpus {cfg.n_docs} outputs, n_max {cfg.n_max}; "
+          f"defaults k {cfg.k}, lambda {cfg.lam}, p_min {cfg.p_min}, alpha {cfg.bias_alpha}; GPU greedy {rig.greedy_tps:.0f} tokens/s", flush=True)
+    if "position" in which:
+        r = rig.run()
+        print("per-position acceptance at the defaults", flush=True)
+        print(fmt("default", r))
+        print("  accept-length histogram: " + " ".join(str(h) for h in r["hist"]))
+        print("  cond(i): " + " ".join(f"{x:.2f}" for x in r["cond"]), flush=True)
+    if "lambda" in which:
+        print("mixture weight lambda (corpus share)")
+        for lam in (0.0, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0):
+            print(fmt(f"lambda {lam:.2f}", rig.run(lam=lam)), flush=True)
+    if "k" in which:
+        print("draft length k")
+        for k in (1, 2, 4, 6, 8, 12, 15):
+            if cfg.batch * (k + 1) <= cfg.batch * rig.max_rows:
+                print(fmt(f"k {k}", rig.run(k=k)), flush=True)
+    if "p_min" in which:
+        print("pruning threshold p_min of the corpus tables")
+        for p in (1, 2, 5, 10, 50, 500):
+            print(fmt(f"p_min {p}", rig.run(p_min=p)), flush=True)
+    if "source" in which:
+        print("drafter source")
+        print(fmt("corpus only", rig.run(lam=1.0)))
+        print(fmt("context only", rig.run(lam=0.0)))
+        print(fmt(f"mixed ({cfg.lam})", rig.run()), flush=True)
+    if "bias" in which:
+        print("target predictability: LM-head bias strength alpha (the configurations use 8)")
+        for alpha in (8.0, 2.0, 1.0, 0.5, 0.0):
+            rig.set_bias(alpha)
+            print(fmt(f"alpha {alpha}", rig.run()) + f"  [greedy {rig.greedy_tps:.0f} tokens/s]", flush=True)
+            print(fmt(f"alpha {alpha} corpus only", rig.run(lam=1.0)), flush=True)
+
+
+if __name__ == "__main__":
+    main()
