@@ -102,6 +102,36 @@ typedef struct {
 } tasc_ngram_stats;
 tasc_status tasc_ngram_get_stats(const tasc_ngram* ng, tasc_ngram_stats* out);
 
+/*
+ * Size and dominance of the typical set of one table (paper, "Task-Induced n-Grams Concentration":
+ * the n-gram entropy and the number of unique n-grams that attain 80 % of the n-gram CDF; Appendix,
+ * "Predicting Model Speedup ... from the Data": Renyi entropy H_alpha(p) = log(sum p^alpha) / (1 - alpha),
+ * used there with alpha = 2).  The distribution is p(x) = count(x) / total over the entries x of the
+ * table of n-grams of length `order` that the build kept (build with p_min = 1 for the corpus' full
+ * distribution); order 1 is the token (unigram) distribution, which is never pruned.
+ *   coverage_ppm  share of the total count to reach, in parts per million, in [0, 1000000]
+ *                 (800000 = the paper's 80 %).
+ *   out           HOST; written only on success.
+ *     n_entries   entries with a non-zero count
+ *     total       sum of their counts
+ *     n_cover     fewest entries, most frequent first, whose counts sum to >= total * coverage_ppm / 1e6
+ *                 (exact integer arithmetic)
+ *     shannon     -sum p ln p, nats (fp64)
+ *     renyi2      -ln sum p^2, nats (fp64)
+ * Runs its kernels on `stream` and synchronises it before returning (an analysis call, not part of
+ * the decode loop); allocates and frees a few KB of device scratch.  An empty table gives all zeros.
+ * Errors: TASC_EINVAL (null, order outside [1, n_max], coverage out of range), TASC_EHIP.
+ */
+typedef struct {
+    int64_t n_entries;
+    int64_t total;
+    int64_t n_cover;
+    double shannon;
+    double renyi2;
+} tasc_table_entropy;
+tasc_status tasc_ngram_entropy(const tasc_ngram* ng, int32_t order, int32_t coverage_ppm,
+                               tasc_table_entropy* out, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Target model.  The paper uses the target as a black box; the architecture (pre-norm RMSNorm,
  * RoPE with rotate-half pairing, grouped-query attention, SwiGLU, untied LM head, sparse additive

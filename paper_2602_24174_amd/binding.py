@@ -19,7 +19,7 @@ TASC_MAX_ORDER, TASC_MAX_K = 8, 15
 
 EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
-    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
+    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
     "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy",
 ]
@@ -37,6 +37,11 @@ class NgramStats(C.Structure):
     _fields_ = [("n_tokens", C.c_int64), ("windows", C.c_int64 * (TASC_MAX_ORDER + 1)),
                 ("distinct", C.c_int64 * (TASC_MAX_ORDER + 1)), ("kept", C.c_int64 * (TASC_MAX_ORDER + 1)),
                 ("contexts", C.c_int64 * (TASC_MAX_ORDER + 1)), ("build_ms", C.c_double), ("count_ms", C.c_double)]
+
+
+class TableEntropy(C.Structure):
+    _fields_ = [("n_entries", C.c_int64), ("total", C.c_int64), ("n_cover", C.c_int64), ("shannon", C.c_double),
+                ("renyi2", C.c_double)]
 
 
 class ModelDesc(C.Structure):
@@ -89,6 +94,7 @@ def lib():
                                                  C.POINTER(C.c_int64)]
         L.tasc_ngram_unigram.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]
         L.tasc_ngram_get_stats.argtypes = [C.c_void_p, C.POINTER(NgramStats)]
+        L.tasc_ngram_entropy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(TableEntropy), C.c_void_p]
         L.tasc_model_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(WeightPtrs), C.POINTER(C.c_void_p)]
         L.tasc_session_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                           C.c_size_t, C.POINTER(C.c_void_p)]
@@ -187,6 +193,12 @@ def tasc_ngram_unigram(ng: Ngram, vocab: int):
     counts = np.zeros(vocab, dtype=np.uint32)
     _check(lib().tasc_ngram_unigram(ng.handle, C.byref(fb), _ptr(counts)))
     return fb.value, counts
+
+
+def tasc_ngram_entropy(ng: Ngram, order: int, coverage_ppm: int = 800000, stream=None) -> TableEntropy:
+    out = TableEntropy()
+    _check(lib().tasc_ngram_entropy(ng.handle, order, coverage_ppm, C.byref(out), _stream(stream)))
+    return out
 
 
 def tasc_ngram_get_stats(ng: Ngram) -> NgramStats:
