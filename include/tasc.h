@@ -304,6 +304,35 @@ enum {
 tasc_status tasc_config_set(int32_t key, int32_t value);
 
 /* ------------------------------------------------------------------------------------------
+ * The model-derived bigram drafter of the paper's comparison (Related Work; Results, "TASC-spec":
+ * a bigram model that assigns each token its most probable next token under the given model, from
+ * the model's conditional distribution for every vocabulary element; evaluated alone and mixed with
+ * the context drafter).
+ * ---------------------------------------------------------------------------------------- */
+/*
+ * next_tok[x] = the target's greedy next token (lowest index on ties) after the one-token sequence
+ * [x], for every x in [0, vocab): ceil(vocab / batch) prefill passes of `batch` one-token prompts
+ * through the session's ordinary forward path.
+ *   s         any session of `m` with max_len >= 2 + 2 * max_rows (max_rows = 1 wastes no rows); its
+ *             sequences are overwritten, so call tasc_session_prefill again before decoding with it.
+ *   next_tok  DEVICE int32[vocab], written.
+ * Synchronises `stream` before returning.  Errors: TASC_EINVAL, TASC_EHIP.
+ */
+tasc_status tasc_model_bigram(const tasc_model* m, tasc_session* s, int32_t* next_tok, void* stream);
+/*
+ * The drafter as tables, usable wherever tasc_ngram_build's result is (tasc_draft, tasc_generate,
+ * the exports): order 2 holds, for every token x, the single successor next_tok[x] with count 1
+ * (T(x) = 1, a point mass: lambda weighs it against the context statistics exactly as it weighs the
+ * corpus tables), orders 3..n_max are empty, so only the context source uses them.  The fallback
+ * token is the most frequent token of the V pairs [x, next_tok[x]].
+ *   next_tok  HOST or DEVICE (`where`) int32[vocab], every value in [0, vocab).
+ *   n_max     in [2, TASC_MAX_ORDER], n_max * ceil(log2(vocab)) <= 128.
+ * Errors as tasc_ngram_build (TASC_EINVAL for a successor outside the vocabulary).
+ */
+tasc_status tasc_ngram_from_bigram(const int32_t* next_tok, tasc_mem where, int32_t vocab, int32_t n_max,
+                                   void* stream, tasc_ngram** out);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement: per-kernel-class device time, taken with HIP event pairs recorded on the stream
  * each kernel is launched on.  Off by default (no events are recorded).  The classes follow the
  * steps of the hot path: table build is timed by tasc_ngram_get_stats, the rest here.

@@ -1,5 +1,5 @@
 """Acceptance instrumentation of TASC-spec on the synthetic workloads: per-position acceptance and the
-lambda / k / p_min / drafter-source / bias-strength sweeps (paper, Results, "TASC-spec": acceptance rate against
+lambda / k / p_min / drafter-source / drafter-kind / bias-strength sweeps (paper, Results, "TASC-spec": acceptance rate against
 draft position; Appendix, mixture-weight ablation; the drafter comparison table).
 
     python -m paper_2602_24174_amd.acceptance_sweeps [--config cfg2] [--docs N] [--gen G] [--sweeps lambda,k,...]
@@ -81,14 +81,29 @@ class SweepRig:
             self.tables[p_min] = self.T.tasc_ngram_build(self.d_corpus, self.corpus[1], c.vocab, c.n_max, p_min)
         return self.tables[p_min]
 
-    def run(self, k=None, lam=None, p_min=None, p_min_ctx=None):
+    def bigram_table(self):
+        """Tables of the model-derived bigram drafter of the current target (tasc_model_bigram + tasc_ngram_from_bigram)."""
+        T, c, torch = self.T, self.cfg, self.torch
+        batch = 256 if c.vocab >= 4096 else 16
+        sess = T.tasc_session_create(self.model, batch, 4, 1)
+        nxt = torch.zeros(c.vocab, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        import time
+        t0 = time.perf_counter()
+        T.tasc_model_bigram(self.model, sess, nxt)
+        self.bigram_ms = (time.perf_counter() - t0) * 1e3
+        sess.close()
+        return T.tasc_ngram_from_bigram(nxt, c.vocab, c.n_max)
+
+    def run(self, k=None, lam=None, p_min=None, p_min_ctx=None, table=None):
         c, T = self.cfg, self.T
         k = c.k if k is None else k
         lam = c.lam if lam is None else lam
         p_min = c.p_min if p_min is None else p_min
         params = T.spec_params(k, int(round(lam * 65536)), c.p_min_ctx if p_min_ctx is None else p_min_ctx, 1)
-        T.tasc_generate(self.model, self.table(p_min), self.session, self.d_prompts, self.poff, c.gen_len, params, self.out, None, 0)  # warm
-        st = T.tasc_generate(self.model, self.table(p_min), self.session, self.d_prompts, self.poff, c.gen_len, params, self.out, None, 0)
+        table = table or self.table(p_min)
+        T.tasc_generate(self.model, table, self.session, self.d_prompts, self.poff, c.gen_len, params, self.out, None, 0)  # warm
+        st = T.tasc_generate(self.model, table, self.session, self.d_prompts, self.poff, c.gen_len, params, self.out, None, 0)
         same = bool((self.out.cpu().numpy() == self.greedy_tokens).all())
         hist = list(st.accept_hist[:k + 1])
         rate, cond = position_rates(hist, k)
@@ -109,7 +124,7 @@ def main():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--docs", type=int, default=0, help="corpus size override (0 = the configuration's)")
     ap.add_argument("--gen", type=int, default=0, help="tokens to generate (0 = the configuration's)")
-    ap.add_argument("--sweeps", default="position,lambda,k,p_min,source,bias")
+    ap.add_argument("--sweeps", default="position,lambda,k,p_min,source,drafters,bias")
     args = ap.parse_args()
     import workload as W
     cfg = W.get_config(args.config)
@@ -145,6 +160,18 @@ def main():
         print(fmt("corpus only", rig.run(lam=1.0)))
         print(fmt("context only", rig.run(lam=0.0)))
         print(fmt(f"mixed ({cfg.lam})", rig.run()), flush=True)
+    if "drafters" in which:
+        print("the four drafters of the paper's comparison table (model bigram = next token of the target after each single token)")
+        for alpha in (cfg.bias_alpha, 1.0):
+            rig.set_bias(alpha)
+            bg = rig.bigram_table()
+            print(f" target with alpha {alpha}: model bigram of {cfg.vocab} tokens in {rig.bigram_ms:.0f} ms; GPU greedy {rig.greedy_tps:.0f} tokens/s")
+            print(fmt("corpus tables only", rig.run(lam=1.0)))
+            print(fmt(f"TASC-spec (lambda {cfg.lam})", rig.run()))
+            print(fmt("model bigram only", rig.run(lam=1.0, table=bg)))
+            print(fmt(f"model bigram + context", rig.run(table=bg)), flush=True)
+            bg.close()
+        rig.set_bias(cfg.bias_alpha)
     if "bias" in which:
         print("target predictability: LM-head bias strength alpha (the configurations use 8)")
         for alpha in (8.0, 2.0, 1.0, 0.5, 0.0):

@@ -19,7 +19,7 @@ TASC_MAX_ORDER, TASC_MAX_K = 8, 15
 
 EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
-    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
+    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
     "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy",
 ]
@@ -94,6 +94,8 @@ def lib():
                                                  C.POINTER(C.c_int64)]
         L.tasc_ngram_unigram.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]
         L.tasc_ngram_get_stats.argtypes = [C.c_void_p, C.POINTER(NgramStats)]
+        L.tasc_model_bigram.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tasc_ngram_from_bigram.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tasc_ngram_entropy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(TableEntropy), C.c_void_p]
         L.tasc_model_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(WeightPtrs), C.POINTER(C.c_void_p)]
         L.tasc_session_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
@@ -199,6 +201,17 @@ def tasc_ngram_entropy(ng: Ngram, order: int, coverage_ppm: int = 800000, stream
     out = TableEntropy()
     _check(lib().tasc_ngram_entropy(ng.handle, order, coverage_ppm, C.byref(out), _stream(stream)))
     return out
+
+
+def tasc_model_bigram(model: "Model", s: "Session", next_tok, stream=None):
+    """next_tok: cuda int32 tensor [vocab], written in place."""
+    _check(lib().tasc_model_bigram(model.handle, s.handle, _ptr(next_tok), _stream(stream)))
+
+
+def tasc_ngram_from_bigram(next_tok, vocab, n_max, stream=None) -> Ngram:
+    out = C.c_void_p()
+    _check(lib().tasc_ngram_from_bigram(_ptr(next_tok), _where(next_tok), vocab, n_max, _stream(stream), C.byref(out)))
+    return Ngram(out.value, n_max)
 
 
 def tasc_ngram_get_stats(ng: Ngram) -> NgramStats:

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtasc.so")
-SOURCES = ["ngram.hip", "draft.hip", "forward.hip", "api.hip", "profile.hip", "table_stats.hip"]
+SOURCES = ["ngram.hip", "draft.hip", "forward.hip", "api.hip", "profile.hip", "table_stats.hip", "bigram.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
