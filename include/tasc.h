@@ -333,6 +333,31 @@ tasc_status tasc_ngram_from_bigram(const int32_t* next_tok, tasc_mem where, int3
                                    void* stream, tasc_ngram** out);
 
 /* ------------------------------------------------------------------------------------------
+ * Counting core of the paper's tokenizer enrichment ("Enriching the Tokenizer": the merge reward
+ * f_merge(t^n) = freq(t^n) * (n - 1) and the loop of the algorithm "Tokenizer Enrichment"), WITHOUT
+ * the prefix-collision filter (it needs token strings; every candidate passes).  Starting from the
+ * base vocabulary [0, vocab), step i counts the token n-grams, 2 <= n <= n_max, of the corpus as
+ * tokenised so far (windows inside one output, as in tasc_ngram_build), takes the n-gram with the
+ * largest reward (ties: the shorter n-gram, then the lexicographically smallest token tuple), names it
+ * token vocab + i and re-tokenises the corpus: its occurrences are replaced left to right, without
+ * overlap, inside each output.  Ends after `budget` merges or when no n-gram is left.
+ *   tokens, out_tokens  HOST or DEVICE (`where`, both alike) int32; out_tokens has room for the input
+ *                       length and receives the final corpus (corpus_len[*n_merges] tokens).
+ *   doc_offsets         HOST int64[n_docs + 1]; out_offsets HOST int64[n_docs + 1] (final boundaries).
+ *   merges              HOST int32[budget][1 + TASC_MAX_ORDER]: n, then the n tokens (over the vocabulary
+ *                       of that step), then -1 padding; merge_freq HOST int64[budget]: freq of the pick.
+ *   corpus_len          HOST int64[budget + 1]: corpus length before merge i; entry *n_merges = final.
+ *   n_merges            HOST: merges performed (<= budget).
+ * Limits: n_max in [2, TASC_MAX_ORDER], n_max * ceil(log2(vocab + budget)) <= 128, corpus < 2^32 - 1
+ * tokens.  Synchronous (one host round trip per merge); allocates about 20 bytes of device scratch per
+ * corpus token plus the tables of one tasc_ngram_build.  Errors: TASC_EINVAL, TASC_ENOMEM, TASC_EHIP.
+ * ---------------------------------------------------------------------------------------- */
+tasc_status tasc_tok_enrich(const int32_t* tokens, const int64_t* doc_offsets, int64_t n_docs, int32_t vocab,
+                            int32_t n_max, int32_t budget, tasc_mem where, void* stream, int32_t* merges,
+                            int64_t* merge_freq, int64_t* corpus_len, int32_t* out_tokens,
+                            int64_t* out_offsets, int32_t* n_merges);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement: per-kernel-class device time, taken with HIP event pairs recorded on the stream
  * each kernel is launched on.  Off by default (no events are recorded).  The classes follow the
  * steps of the hot path: table build is timed by tasc_ngram_get_stats, the rest here.

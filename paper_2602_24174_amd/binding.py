@@ -19,7 +19,7 @@ TASC_MAX_ORDER, TASC_MAX_K = 8, 15
 
 EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
-    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
+    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_tok_enrich", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
     "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy",
 ]
@@ -94,6 +94,8 @@ def lib():
                                                  C.POINTER(C.c_int64)]
         L.tasc_ngram_unigram.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]
         L.tasc_ngram_get_stats.argtypes = [C.c_void_p, C.POINTER(NgramStats)]
+        L.tasc_tok_enrich.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
         L.tasc_model_bigram.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tasc_ngram_from_bigram.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tasc_ngram_entropy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(TableEntropy), C.c_void_p]
@@ -201,6 +203,29 @@ def tasc_ngram_entropy(ng: Ngram, order: int, coverage_ppm: int = 800000, stream
     out = TableEntropy()
     _check(lib().tasc_ngram_entropy(ng.handle, order, coverage_ppm, C.byref(out), _stream(stream)))
     return out
+
+
+def tasc_tok_enrich(tokens, doc_offsets, vocab, n_max, budget, stream=None):
+    """tokens: int32 numpy array (host) or cuda tensor.  Returns (merges [(ngram tuple, freq, new id)], final tokens
+    (same kind as the input, trimmed), final offsets int64[D + 1], corpus lengths int64[n_merges + 1])."""
+    doc_offsets = np.ascontiguousarray(doc_offsets, dtype=np.int64)
+    n_docs = doc_offsets.shape[0] - 1
+    rows = np.zeros((max(budget, 1), 1 + TASC_MAX_ORDER), dtype=np.int32)
+    freq = np.zeros(max(budget, 1), dtype=np.int64)
+    lens = np.zeros(budget + 1, dtype=np.int64)
+    out_off = np.zeros(n_docs + 1, dtype=np.int64)
+    if isinstance(tokens, np.ndarray):
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        out = np.zeros(max(tokens.shape[0], 1), dtype=np.int32)
+    else:
+        import torch
+        out = torch.zeros(max(tokens.shape[0], 1), dtype=torch.int32, device=tokens.device)
+    n = C.c_int32(0)
+    _check(lib().tasc_tok_enrich(_ptr(tokens), _ptr(doc_offsets), n_docs, vocab, n_max, budget, _where(tokens), _stream(stream),
+                                 _ptr(rows), _ptr(freq), _ptr(lens), _ptr(out), _ptr(out_off), C.byref(n)))
+    m = n.value
+    merges = [(tuple(int(t) for t in rows[i, 1:1 + rows[i, 0]]), int(freq[i]), vocab + i) for i in range(m)]
+    return merges, out[:int(lens[m])], out_off, lens[:m + 1]
 
 
 def tasc_model_bigram(model: "Model", s: "Session", next_tok, stream=None):
