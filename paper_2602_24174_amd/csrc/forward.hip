@@ -202,19 +202,31 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         ks = ks < TG_MAX_SLICES ? ks : TG_MAX_SLICES;
         return ks < 1 ? 1 : ks;
     };
-    // out (+)= A W^T through k-slices and the ordered reduction
-    auto gemm_sliced = [&](const BF16* A, const void* Wm, int N, int K, float* out, bool resid) {
+    // out (+)= A W^T through k-slices and the ordered reduction.  With `norm_g` the RMSNorm of the updated rows (gain
+    // norm_g, into d.h) is fused into the reduction; returns false if the caller still has to run it (no slices).
+    auto gemm_sliced = [&](const BF16* A, const void* Wm, int N, int K, float* out, bool resid, const float* norm_g) {
         const int ks = slices(N, K);
         if (ks == 1) {
             if (resid) launch_gemm<TEPI_RESID>(A, Wm, M, N, K, out, nullptr, none, 1, st);
             else launch_gemm<TEPI_STORE>(A, Wm, M, N, K, out, nullptr, none, 1, st);
-            return;
+            return false;
         }
         launch_gemm<TEPI_PARTIAL>(A, Wm, M, N, K, d.att_part, nullptr, none, ks, st);
         const size_t mn = (size_t)M * N;
+        if (resid && norm_g && N == D && D <= RRN_MAX_D) {
+            bool fused = true;
+            switch (ks) {
+#define RRN_CASE(NS) case NS: k_reduce_resid_norm<NS><<<dim3(M), dim3(256), 0, st>>>(d.att_part, mn, out, norm_g, D, c.rms_eps, (BF16*)d.h); break;
+                RRN_CASE(2) RRN_CASE(3) RRN_CASE(4) RRN_CASE(5) RRN_CASE(6) RRN_CASE(7) RRN_CASE(8)
+#undef RRN_CASE
+                default: fused = false;
+            }
+            if (fused) return true;
+        }
         const unsigned blocks = (unsigned)((mn / 4 + 255) / 256);
         if (resid) k_splitk_reduce<true><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
         else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
+        return false;
     };
     const int rows_pass = 32;
     const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
@@ -223,21 +235,25 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         k_embed<BF16><<<dim3(M), dim3(64), 0, st>>>((const BF16*)m->embed, d.row_tok, D, d.x);
     }
     TASC_LAUNCH_CHECK();
+    bool h_ready = false;                 // d.h already holds the layer's normalised input
     for (int l = 0; l < c.n_layers; ++l) {
         const TascLayerW& w = m->layers[l];
         BF16* kv_layer = (BF16*)s->kv_pool + (size_t)l * s->kv_layer_stride;
-        {
+        if (!h_ready) {
             PROF(TASC_KC_NORM);
             k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (BF16*)d.h);
         }
+        const int ks_qkv = slices(nqkv, D);
         {
             PROF(TASC_KC_GEMM_QKV);
-            gemm_sliced((const BF16*)d.h, w.wqkv, nqkv, D, d.qkv, false);
+            if (ks_qkv == 1) launch_gemm<TEPI_STORE>((const BF16*)d.h, w.wqkv, M, nqkv, D, d.qkv, nullptr, none, 1, st);
+            else launch_gemm<TEPI_PARTIAL>((const BF16*)d.h, w.wqkv, M, nqkv, D, d.att_part, nullptr, none, ks_qkv, st);
         }
         {
+            // the k-slices of a split projection are added inside the rotation kernel (same order as the reduction kernel)
             PROF(TASC_KC_ROPE_KV);
-            k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(d.qkv, m->rope_cos, m->rope_sin, c.max_pos, d.n_rows, d.pos0, d.block_tab,
-                                                         gm, (BF16*)d.q, kv_layer);
+            k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(ks_qkv == 1 ? d.qkv : d.att_part, m->rope_cos, m->rope_sin, c.max_pos, d.n_rows,
+                                                         d.pos0, d.block_tab, gm, (BF16*)d.q, kv_layer, ks_qkv, (size_t)M * nqkv);
         }
         {
             PROF(TASC_KC_ATTN);
@@ -247,11 +263,12 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
             else if (hd == 64) k_attn_tiled<2><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
             else k_attn_tiled<4><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
         }
+        bool normed;
         {
             PROF(TASC_KC_GEMM_O);
-            gemm_sliced((const BF16*)d.att, w.wo, D, nqo, d.x, true);
+            normed = gemm_sliced((const BF16*)d.att, w.wo, D, nqo, d.x, true, w.g2);
         }
-        {
+        if (!normed) {
             PROF(TASC_KC_NORM);
             k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (BF16*)d.h);
         }
@@ -260,8 +277,9 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
             launch_gemm<TEPI_SWIGLU>((const BF16*)d.h, w.wgu, M, 2 * F, D, nullptr, (BF16*)d.act, none, 1, st);
         }
         {
+            // the next layer's first RMSNorm rides on this reduction
             PROF(TASC_KC_GEMM_D);
-            gemm_sliced((const BF16*)d.act, w.wd, D, F, d.x, true);
+            h_ready = gemm_sliced((const BF16*)d.act, w.wd, D, F, d.x, true, l + 1 < c.n_layers ? m->layers[l + 1].g1 : nullptr);
         }
         TASC_LAUNCH_CHECK();
     }

@@ -144,10 +144,12 @@ struct KvGeom {
 
 // Row r = (sequence b, i) sits at position pos0[b] + i.  q is rotated into `q_out`; k is rotated and
 // written to the K half of its page, v to the transposed V half.  Rows beyond n_rows[b] write nothing.
+// `qkv` may be n_slices partial sums [n_slices][rows][nqkv] (slice_stride elements apart), added here in slice order.
 template <typename T>
 __global__ void k_rope_kv(const float* __restrict__ qkv, const float* __restrict__ cosT, const float* __restrict__ sinT,
                           int max_pos, const int32_t* __restrict__ n_rows, const int32_t* __restrict__ pos0,
-                          const int32_t* __restrict__ block_tab, KvGeom gm, T* __restrict__ q_out, T* __restrict__ kv_layer) {
+                          const int32_t* __restrict__ block_tab, KvGeom gm, T* __restrict__ q_out, T* __restrict__ kv_layer,
+                          int n_slices = 1, size_t slice_stride = 0) {
     const int r = blockIdx.x, b = r / gm.nq, i = r % gm.nq;
     const bool active = i < n_rows[b];
     const int pos = pos0[b] + i;
@@ -159,7 +161,11 @@ __global__ void k_rope_kv(const float* __restrict__ qkv, const float* __restrict
     if (active) page = kv_layer + (size_t)block_tab[(size_t)b * gm.max_blocks + pos / TASC_KV_BLOCK] * gm.page_elems;
     for (int idx = threadIdx.x; idx < (gm.H + 2 * gm.Hkv) * half; idx += blockDim.x) {
         const int head = idx / half, e = idx % half;
-        const float a = src[head * gm.hd + e], c = src[head * gm.hd + e + half];
+        float a = src[head * gm.hd + e], c = src[head * gm.hd + e + half];
+        for (int sl = 1; sl < n_slices; ++sl) {            // k-slices of a split projection, added in slice order
+            a += src[(size_t)sl * slice_stride + head * gm.hd + e];
+            c += src[(size_t)sl * slice_stride + head * gm.hd + e + half];
+        }
         if (head < gm.H + gm.Hkv) {
             const float cs = cosT[(size_t)tpos * half + e], sn = sinT[(size_t)tpos * half + e];
             const float ra = a * cs - c * sn, rc = c * cs + a * sn;

@@ -321,6 +321,61 @@ __global__ void k_splitk_reduce(const float* __restrict__ part, int n_slices, si
     *o = s;
 }
 
+// The ordered reduction with residual add, fused with the RMSNorm that follows it: one workgroup of 256 threads per
+// row, a thread per group of 4 features (two groups for d > 1024), every load of a thread issued before the first add.
+// x[r] += part[0][r] + part[1][r] + ... (the element order of k_splitk_reduce, so x has the same bits), then
+// h[r] = bf16(x[r] * rinv * g); the squares are summed per thread, per wave and over the 4 waves in a fixed order, so
+// a row's result does not depend on the launch.  d <= 2048, d % 4 == 0.
+#define RRN_MAX_D 2048
+template <int NS>
+__global__ __launch_bounds__(256) void k_reduce_resid_norm(const float* __restrict__ part, size_t mn, float* __restrict__ x,
+                                                           const float* __restrict__ g, int d, float eps, BF16* __restrict__ h) {
+    const int r = blockIdx.x, t = threadIdx.x;
+    float* xr = x + (size_t)r * d;
+    const float* pr = part + (size_t)r * d;
+    f32x4 v[2][NS + 1];
+    f32x4 gg[2];
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int k = 4 * (t + 256 * u);
+        const bool on = k < d;
+        const int kc = on ? k : 0;                                  // unconditional loads; the clamped ones are unused
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) v[u][sl] = *reinterpret_cast<const f32x4*>(pr + (size_t)sl * mn + kc);
+        v[u][NS] = *reinterpret_cast<const f32x4*>(xr + kc);
+        gg[u] = *reinterpret_cast<const f32x4*>(g + kc);
+    }
+    float ss = 0.f;
+    f32x4 s[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        s[u] = v[u][0];
+#pragma unroll
+        for (int sl = 1; sl < NS; ++sl) s[u] += v[u][sl];
+        s[u] += v[u][NS];
+        if (4 * (t + 256 * u) < d) {
+            *reinterpret_cast<f32x4*>(xr + 4 * (t + 256 * u)) = s[u];
+            ss += s[u][0] * s[u][0] + s[u][1] * s[u][1] + s[u][2] * s[u][2] + s[u][3] * s[u][3];
+        } else {
+            s[u] = zero;
+        }
+    }
+    __shared__ float s_ss[4];
+    ss = wave_sum(ss);
+    if ((t & 63) == 0) s_ss[t >> 6] = ss;
+    __syncthreads();
+    ss = ((s_ss[0] + s_ss[1]) + s_ss[2]) + s_ss[3];
+    const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int k = 4 * (t + 256 * u);
+        if (k < d)
+            *reinterpret_cast<u32x2*>(h + (size_t)r * d + k) =
+                pack_bf16x4(s[u][0] * rinv * gg[u][0], s[u][1] * rinv * gg[u][1], s[u][2] * rinv * gg[u][2], s[u][3] * rinv * gg[u][3]);
+    }
+}
+
 // cursor table of the LM-head bias (see LmEpi): one thread per (row, strip boundary)
 __global__ void k_bias_ptr(BiasCsr bias, const int32_t* __restrict__ sel_tok, int n_sel, int n_strips, int32_t* __restrict__ out) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
