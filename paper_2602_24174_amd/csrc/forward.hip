@@ -190,15 +190,28 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
     const int nqkv = (H + 2 * Hkv) * hd, nqo = H * hd;
     KvGeom gm{H, Hkv, hd, nq, s->max_blocks, s->page_elems};
     LmEpi none{};
-    // narrow outputs (few column tiles) are computed in k-slices; the slice count depends on N and K only
+    // Narrow outputs (few column tiles) are computed in k-slices.  The slice count fixes the order in which a row's
+    // products are added, so it must be the same for every forward of a session (a greedy step, a verify step and a
+    // prompt chunk of one session differ in their row count): it depends on N, K and the session's batch only, never on
+    // the rows of the call.  rows_ref = 5 rows per sequence stands for the verify steps the session is sized for.
+    const int rows_ref = s->batch * 5;
     auto slices = [&](int N, int K) {
         const int n_nt = (N + 127) / 128, nk = K / TG_BK;
         if (n_nt >= 32) return 1;
-        // few column tiles: one slice per 12 k-steps, or enough for about 24 (column tile, slice) pairs if that is
-        // more, but slices of at least 4 k-steps and no more slices than needed: each costs a pass over the fp32
-        // partial sums (measured on the qkv / output / down projections of the 0.5B and 1.5B shapes)
-        int ks = nk / 12 > (24 + n_nt - 1) / n_nt ? nk / 12 : (24 + n_nt - 1) / n_nt;
-        ks = ks < nk / 4 ? ks : nk / 4;
+        // many sequences, short k: the small tiles of one slice already fill the chip, and every slice would cost a
+        // pass over rows x N partial sums
+        if (nk <= 40 && n_nt * ((rows_ref + 127) / 128) >= 128) return 1;
+        int ks;
+        if (rows_ref >= kLargeTileRows && nk > 40) {
+            // long k on large tiles: as many slices as fit the compute units in one round
+            const int tiles = ((rows_ref + 255) / 256) * ((N + 255) / 256);
+            ks = 256 / tiles;
+        } else {
+            // few rows: one slice per 12 k-steps, or enough for about 24 (column tile, slice) pairs if that is more
+            // (measured on the qkv / output / down projections of the 0.5B and 1.5B shapes)
+            ks = nk / 12 > (24 + n_nt - 1) / n_nt ? nk / 12 : (24 + n_nt - 1) / n_nt;
+        }
+        ks = ks < nk / 4 ? ks : nk / 4;                       // slices of at least 4 k-steps
         ks = ks < TG_MAX_SLICES ? ks : TG_MAX_SLICES;
         return ks < 1 ? 1 : ks;
     };

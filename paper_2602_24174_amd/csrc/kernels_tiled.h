@@ -71,7 +71,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     // (native vector types in plain arrays with compile-time indices: a struct-typed uint4 would be copied through
     // private memory)
     struct StageW { u32x4 w[PW]; } sw0, sw1;   // weights: fetched two steps ahead (HBM latency)
-    struct StageA { u32x4 a[PA]; } sa;         // activations: one step ahead (they sit in L2)
+    struct StageA { u32x4 a[PA]; } sa0, sa1;   // activations: two steps ahead as well (an L2 round trip under load takes a step)
     // rows past the matrix are read from its last row (unconditional loads keep the memory pipeline's wait counts
     // exact); what they produce is never stored
     const int wrow_last = N - 1 - n0 - ld_row, arow_last = M - 1 - m0 - ld_row;   // clamp bounds relative to the thread's first row
@@ -113,10 +113,19 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
         nk = min(nk, kt_begin + per);
         outf += (size_t)blockIdx.y * M * N;
     }
-    auto multiply = [&](int buf) __attribute__((always_inline)) {
-        __builtin_amdgcn_iglp_opt(IGLP);
+    const int k_last = (nk - 1) * TG_BK;
+    // One pipeline step = the multiply of LDS buffer `buf` with the refill of the other buffer woven into it, a quarter
+    // per 16 of k: the registers that hold the next step's tile (weights fetched two steps ago, activations one step
+    // ago) go to the other buffer, which nobody has read since the last barrier, and are then refilled from global
+    // memory for the step after that (activations at ka, weights at kw; steps past the last re-read the last one and
+    // are never multiplied).  The LDS stores and the fetches so travel under the step's MFMAs instead of ahead of them.
+    // Nothing sits under a condition: a conditional load ends in a register copy at the join, which waits for the data.
+    static_assert(PW == 4 && PA == 4 && TG_BK == 64, "the refill is split in four quarters, one per MFMA k-block");
+    auto step = [&](int buf, StageW& w, StageA& sa_, int ka, int kw) __attribute__((always_inline)) {
         const uint16_t* bw = sW + (size_t)(buf * BN + wn * SN + (lane & 31)) * TG_LD + 8 * (lane >> 5);
         const uint16_t* ba = sA + (size_t)(buf * BM + wm * SM + (lane & 31)) * TG_LD + 8 * (lane >> 5);
+        uint16_t* dw = sW + (size_t)((buf ^ 1) * BN + ld_row) * TG_LD + ld_col;
+        uint16_t* da = sA + (size_t)((buf ^ 1) * BM + ld_row) * TG_LD + ld_col;
 #pragma unroll
         for (int ks = 0; ks < TG_BK / 16; ++ks) {
             bf16x8 fw[TI], fa[TJ];
@@ -124,69 +133,39 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
             for (int i = 0; i < TI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(bw + (size_t)i * 32 * TG_LD + ks * 16);
 #pragma unroll
             for (int j = 0; j < TJ; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(ba + (size_t)j * 32 * TG_LD + ks * 16);
+            *reinterpret_cast<u32x4*>(dw + (size_t)ks * ROWS_PASS * TG_LD) = w.w[ks];
+            *reinterpret_cast<u32x4*>(da + (size_t)ks * ROWS_PASS * TG_LD) = sa_.a[ks];
+            sa_.a[ks] = *reinterpret_cast<const u32x4*>(abase + aoff[ks] + ka);
+            w.w[ks] = *reinterpret_cast<const u32x4*>(wbase + woff[ks] + kw);
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
                 for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);              // keeps the quarters in this order
         }
     };
-    // one pipeline step: fetch the weights of kt + 2 and the activations of kt + 1, multiply kt out of LDS, then
-    // move kt + 1 (weights fetched a step earlier) into the other LDS buffer
-    // No load sits under a condition (a conditional load ends in a register copy at the join, which waits for the data
-    // and would serialise the prefetch): steps beyond the last re-read the last one and are never stored to LDS.
-    const int k_last = (nk - 1) * TG_BK;
-    constexpr bool DEEP = PW <= 4;              // the 4-wave 256 x 256 tile has no registers for a second weight set
-    if constexpr (DEEP) {
-        // Step kt multiplies LDS buffer kt % 2.  At its start the tile of step kt + 1 (activations fetched a step ago,
-        // weights two steps ago) is parked in the other buffer, which nobody has read since the last barrier, and the
-        // next fetches are issued; the LDS stores and the fetches then run under the step's MFMAs.
-        // The body is free of branches around loads and LDS stores: a value loaded before a multiply but only used
-        // under a condition would be sunk into the conditional block, behind the multiply it was meant to overlap.
-        // Steps past the last one re-read the last one; their LDS tiles are written but never multiplied.
-        if (kt_begin < nk) {
-            load_w(sw0, kt_begin * TG_BK);
-            load_a(sa, kt_begin * TG_BK);
-            store_wa(sw0, sa, 0);
-            load_a(sa, min((kt_begin + 1) * TG_BK, k_last));
-            load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
-            load_w(sw0, min((kt_begin + 2) * TG_BK, k_last));
-        }
+    // Prologue: step kt_begin into buffer 0; registers: set 1 = step + 1, set 0 = step + 2.  Step kt multiplies buffer
+    // (kt - kt_begin) % 2 and parks set (kt - kt_begin + 1) % 2 in the other one.
+    if (kt_begin < nk) {
+        load_w(sw0, kt_begin * TG_BK);
+        load_a(sa0, kt_begin * TG_BK);
+        store_wa(sw0, sa0, 0);
+        load_a(sa1, min((kt_begin + 1) * TG_BK, k_last));
+        load_w(sw1, min((kt_begin + 1) * TG_BK, k_last));
+        load_a(sa0, min((kt_begin + 2) * TG_BK, k_last));
+        load_w(sw0, min((kt_begin + 2) * TG_BK, k_last));
+    }
+    __syncthreads();
+    int kt = kt_begin;
+    for (; kt + 1 < nk; kt += 2) {                    // pairs of steps: the loop body holds no branch
+        step(0, sw1, sa1, min((kt + 3) * TG_BK, k_last), min((kt + 3) * TG_BK, k_last));
         __syncthreads();
-        for (int kt = kt_begin; kt < nk; kt += 2) {
-            store_wa(sw1, sa, 1);                           // step kt + 1
-            load_a(sa, min((kt + 2) * TG_BK, k_last));      // activations first: loads return in order
-            load_w(sw1, min((kt + 3) * TG_BK, k_last));
-            __builtin_amdgcn_sched_barrier(0);              // stores and fetches stay ahead of the multiply
-            multiply(0);
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            store_wa(sw0, sa, 0);                           // step kt + 2
-            load_a(sa, min((kt + 3) * TG_BK, k_last));
-            load_w(sw0, min((kt + 4) * TG_BK, k_last));
-            __builtin_amdgcn_sched_barrier(0);
-            if (kt + 1 < nk) multiply(1);
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-        }
-    } else {
-        // one step ahead for both operands: fetch kt + 1 into registers, multiply kt out of one LDS buffer, then park
-        // kt + 1 in the other (last read before the previous barrier)
-        if (kt_begin < nk) {
-            load_w(sw0, kt_begin * TG_BK);
-            load_a(sa, kt_begin * TG_BK);
-            store_wa(sw0, sa, 0);
-        }
+        step(1, sw0, sa0, min((kt + 4) * TG_BK, k_last), min((kt + 4) * TG_BK, k_last));
         __syncthreads();
-        for (int kt = kt_begin; kt < nk; ++kt) {
-            const int buf = (kt - kt_begin) & 1;
-            load_a(sa, min((kt + 1) * TG_BK, k_last));
-            load_w(sw0, min((kt + 1) * TG_BK, k_last));
-            __builtin_amdgcn_sched_barrier(0);
-            if (buf == 0) multiply(0); else multiply(1);
-            __builtin_amdgcn_sched_barrier(0);
-            store_wa(sw0, sa, buf ^ 1);
-            __syncthreads();
-        }
+    }
+    if (kt < nk) {                                    // odd count: the last step sits in buffer 0; its refill is idle work
+        step(0, sw1, sa1, k_last, k_last);
+        __syncthreads();
     }
 
     // ---- epilogue: acc[i][j][e] = out[m][n], n = n0 + SN wn + 32 i + tile_row(e, lane), m = m0 + SM wm + 32 j + lane % 32
