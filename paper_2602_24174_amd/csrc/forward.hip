@@ -183,6 +183,8 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         if ((rc = tiled_attrs<TEPI_SWIGLU>()) != TASC_OK) return rc;
         if ((rc = tiled_attrs<TEPI_LMHEAD>()) != TASC_OK) return rc;
         if ((rc = tiled_attrs<TEPI_PARTIAL>()) != TASC_OK) return rc;
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<2>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(64) + 4 * TA_MAX_BLOCKS));
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<4>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(128) + 4 * TA_MAX_BLOCKS));
         g_tiled_ready = true;
     }
     const int M = s->batch * nq;
@@ -241,6 +243,8 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
         return false;
     };
+    int att_chunks = 512 / (s->batch * Hkv);          // two workgroups per compute unit in one round
+    att_chunks = att_chunks < 1 ? 1 : (att_chunks > 8 ? 8 : att_chunks);
     const int rows_pass = 32;
     const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
     {
@@ -272,9 +276,23 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
             PROF(TASC_KC_ATTN);
             AttnArgs aa{(const BF16*)d.q, (BF16*)d.att, kv_layer, d.n_rows, d.pos0, d.block_tab, s->batch, nq, H, Hkv,
                         s->max_blocks, s->page_elems, 1.0f / sqrtf((float)hd)};
-            if (hd == 32) k_attn_tiled<1><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
-            else if (hd == 64) k_attn_tiled<2><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
-            else k_attn_tiled<4><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+            if (hd == 32 || s->max_blocks > TA_MAX_BLOCKS) {
+                if (hd == 64) k_attn_tiled<2><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+                else if (hd == 128) k_attn_tiled<4><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+                else k_attn_tiled<1><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+            } else {
+                // keys and values staged in LDS, 64 rows per pass; the key tiles are dealt to att_chunks workgroups, a
+                // number fixed by the session's batch (it sets the order in which a row's keys are added)
+                const size_t rows_all = (size_t)M;
+                AttnStagedArgs sa{aa, d.att_part, d.att_part + (size_t)att_chunks * rows_all * H * hd, att_chunks};
+                const dim3 grid(s->batch * Hkv, (nq * (H / Hkv) + 63) / 64, att_chunks);
+                if (hd == 64) k_attn_staged<2><<<grid, dim3(SMALL_THREADS), TA_LDS_BYTES(64) + 4 * s->max_blocks, st>>>(sa);
+                else k_attn_staged<4><<<grid, dim3(SMALL_THREADS), TA_LDS_BYTES(128) + 4 * s->max_blocks, st>>>(sa);
+                if (att_chunks > 1) {
+                    const size_t n = rows_all * H * hd / 4;
+                    k_attn_merge<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(sa.part_o, sa.part_ml, att_chunks, rows_all, H, hd, (BF16*)d.att);
+                }
+            }
         }
         bool normed;
         {

@@ -582,3 +582,228 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
         }
     }
 }
+
+// ---------------------------------------------------------------- paged GQA attention with keys and values staged in LDS
+// One workgroup per (sequence, KV head, pass of 64 query rows, key chunk c of C).  Key tiles of 64 at absolute
+// positions 64 t; chunk c owns the tiles t = c, c + C, ..., so which tiles a workgroup sees does not depend on the
+// launch's row count, and a tile past a row's position contributes exactly nothing to that row.  The 8 waves load a tile
+// (keys [64][hd], values [hd][64]) from the pages into registers while the previous one is multiplied out of LDS, so the
+// tile is read once for all 64 rows.  Wave w multiplies row tile w % 4 (16 rows) by the 32 keys w / 4 of the tile
+// (S^T = K Q^T, O^T = V^T P^T with 16x16x32 MFMAs, as in the small-batch kernel); the two key halves of a row tile are
+// merged through LDS at the end.  C == 1: the result goes to `att`; C > 1: unnormalised sums, running maxima and
+// denominators go to part_o / part_ml for k_attn_merge, which adds the chunks in the order c = 0, 1, ...
+struct AttnStagedArgs {
+    AttnArgs a;
+    float* part_o;            // [C][B * nq][H * hd]
+    float* part_ml;           // [C][B * nq][H][2]
+    int32_t C;
+};
+#define TA_KPAD 8             // bf16 elements of padding per key row / value row in LDS
+#define TA_LDS_BYTES(hd) (2 * (64 * ((hd) + TA_KPAD) + (hd) * (64 + TA_KPAD)) * 2)
+#define TA_MAX_BLOCKS 2048    // page ids of one sequence kept in LDS (sequences of up to 32,768 tokens)
+
+template <int NKS>
+__global__ __launch_bounds__(SMALL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_attn_staged(AttnStagedArgs aa) {
+    constexpr int hd = 32 * NKS, ndt = 2 * NKS;
+    constexpr int KLD = hd + TA_KPAD, VLD = 64 + TA_KPAD;
+    constexpr int LPT = hd / 64;                      // 16-byte loads per thread for the keys of a tile, and for the values
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    uint16_t* sK = reinterpret_cast<uint16_t*>(lds);                 // [2][64][KLD]
+    uint16_t* sV = sK + 2 * 64 * KLD;                                // [2][hd][VLD]
+    int32_t* s_bt = reinterpret_cast<int32_t*>(lds + TA_LDS_BYTES(hd));   // [max_blocks]: the sequence's page ids
+    const AttnArgs& a = aa.a;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, qd = lane >> 4;
+    const int rt = wave & 3, par = wave >> 2;
+    const int Gq = a.H / a.Hkv, R = a.nq * Gq;
+    const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv;
+    const int r0 = blockIdx.y * 64, c = blockIdx.z, C = aa.C;
+    const int nr = a.n_rows[b], p0 = a.pos0[b];
+    const int32_t* bt = a.block_tab + (size_t)b * a.max_blocks;
+    const size_t v_off = (size_t)a.Hkv * TASC_KV_BLOCK * hd;
+    const int i_last = min(nr - 1, (min(r0 + 64, R) - 1) / Gq);
+    const int L = i_last >= 0 ? p0 + i_last + 1 : 0;                 // keys this pass can see
+    const int n_macro = (L + 63) / 64;
+    const int n_my = n_macro > c ? (n_macro - c + C - 1) / C : 0;    // tiles c, c + C, ..
+    // page ids into LDS once: a tile's fetch then starts without a dependent global load
+    for (int i = tid; i < min(4 * n_macro, a.max_blocks); i += SMALL_THREADS) s_bt[i] = bt[i];
+    __syncthreads();
+    const int pg_last = min(4 * n_macro, a.max_blocks) - 1;
+
+    // the wave's 16 query rows
+    const int r = r0 + 16 * rt + m;
+    const int qi_row = r / Gq, jq = r % Gq;
+    const bool row_ok = r < R && qi_row < nr;
+    const int qi = row_ok ? p0 + qi_row : -1;
+    const bool tile_rows = r0 + 16 * rt < R;                         // the wave has rows at all
+    bf16x8 qf[NKS];
+    {
+        const BF16* qp = a.q + (size_t)(b * a.nq + (row_ok ? qi_row : 0)) * a.H * hd + (size_t)(g * Gq + (row_ok ? jq : 0)) * hd;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            bf16x8 v = *reinterpret_cast<const bf16x8*>(qp + 32 * ks + 8 * qd);
+            if (!row_ok) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            qf[ks] = v;
+        }
+    }
+    float mx = -INFINITY, lsum = 0.f;
+    f32x4 o[ndt];
+#pragma unroll
+    for (int dt = 0; dt < ndt; ++dt) o[dt] = f32x4{0, 0, 0, 0};
+
+    // staging: thread -> LPT chunks of 16 bytes of the keys and LPT of the values, consecutive threads on consecutive
+    // chunks of a page (a page holds 16 tokens: keys [16][hd] per KV head, values [hd][16])
+    u32x4 rk[LPT], rv[LPT];
+    auto fetch = [&](int idx) __attribute__((always_inline)) {
+        const int t = c + min(idx, n_my - 1) * C;                    // past the end: the last tile again (unconditional loads)
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            const int q = tid + SMALL_THREADS * u;                   // chunk of the tile's keys: key q / (hd / 8), dims 8 (q % (hd / 8))
+            const int key = q / (hd / 8), dch = q % (hd / 8);
+            const int pg = min(4 * t + key / TASC_KV_BLOCK, pg_last);
+            const BF16* page = a.kv_layer + (size_t)s_bt[pg] * a.page_elems;
+            rk[u] = *reinterpret_cast<const u32x4*>(page + (size_t)(g * TASC_KV_BLOCK + key % TASC_KV_BLOCK) * hd + 8 * dch);
+            // chunk of the tile's values: page q / (2 hd), dim (q % (2 hd)) / 2, tokens 8 (q % 2) ..
+            const int vp = q / (2 * hd), dim = (q % (2 * hd)) / 2, half = q % 2;
+            const int pgv = min(4 * t + vp, pg_last);
+            const BF16* pagev = a.kv_layer + (size_t)s_bt[pgv] * a.page_elems;
+            rv[u] = *reinterpret_cast<const u32x4*>(pagev + v_off + (size_t)(g * hd + dim) * TASC_KV_BLOCK + 8 * half);
+        }
+    };
+    auto park = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            const int q = tid + SMALL_THREADS * u;
+            const int key = q / (hd / 8), dch = q % (hd / 8);
+            *reinterpret_cast<u32x4*>(sK + (size_t)(buf * 64 + key) * KLD + 8 * dch) = rk[u];
+            const int vp = q / (2 * hd), dim = (q % (2 * hd)) / 2, half = q % 2;
+            *reinterpret_cast<u32x4*>(sV + (size_t)(buf * hd + dim) * VLD + TASC_KV_BLOCK * vp + 8 * half) = rv[u];
+        }
+    };
+    auto multiply = [&](int buf, int t) __attribute__((always_inline)) {
+        const int key0 = 64 * t + 32 * par;
+        const uint16_t* kb = sK + (size_t)(buf * 64 + 32 * par + m) * KLD + 8 * qd;
+        const uint16_t* vb = sV + (size_t)(buf * hd + m) * VLD + 32 * par + 4 * qd;
+        f32x4 s0 = f32x4{0, 0, 0, 0}, s1 = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(kb + 32 * ks);
+            const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(kb + (size_t)16 * KLD + 32 * ks);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[ks], s1, 0, 0, 0);
+        }
+        float sv[8];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int key = key0 + (u < 4 ? 4 * qd + u : 16 + 4 * qd + (u - 4));
+            const float sc = (u < 4 ? s0[u] : s1[u - 4]) * a.scale;
+            sv[u] = (key <= qi) ? sc : -INFINITY;
+            tmax = fmaxf(tmax, sv[u]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(mx, tmax);
+        float psum = 0.f, corr = 1.f;
+        uint32_t pw[4] = {0, 0, 0, 0};
+        if (m_new != -INFINITY) {
+            corr = __expf(mx - m_new);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t pb = f2bf(__expf(sv[u] - m_new));
+                pw[u >> 1] |= pb << (16 * (u & 1));
+                psum += bf2f(pb);
+            }
+        }
+        const bf16x8 pk = as_bf16x8(pw[0], pw[1], pw[2], pw[3]);
+        psum += __shfl_xor(psum, 16);
+        psum += __shfl_xor(psum, 32);
+        lsum = lsum * corr + psum;
+        mx = m_new;
+#pragma unroll
+        for (int dt = 0; dt < ndt; ++dt) {
+            const u32x2 h0 = *reinterpret_cast<const u32x2*>(vb + (size_t)16 * dt * VLD);
+            const u32x2 h1 = *reinterpret_cast<const u32x2*>(vb + (size_t)16 * dt * VLD + 16);
+            o[dt] *= corr;
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(h0[0], h0[1], h1[0], h1[1]), pk, o[dt], 0, 0, 0);
+        }
+    };
+    if (n_my > 0) {
+        fetch(0);
+        park(0);
+        __syncthreads();
+        for (int idx = 0; idx < n_my; ++idx) {
+            fetch(idx + 1);
+            const int t = c + idx * C;
+            if (tile_rows && 64 * t + 32 * par < L) multiply(idx & 1, t);
+            park((idx + 1) & 1);
+            __syncthreads();
+        }
+    }
+    // merge the two key halves of every row tile: waves 4..7 hand theirs to waves 0..3 through LDS (the tile buffers are free)
+    float* so = reinterpret_cast<float*>(lds) + (size_t)rt * (16 * hd + 32);
+    if (par == 1) {
+#pragma unroll
+        for (int dt = 0; dt < ndt; ++dt) *reinterpret_cast<f32x4*>(so + (size_t)m * hd + 16 * dt + 4 * qd) = o[dt];
+        if (qd == 0) { so[16 * hd + 2 * m] = mx; so[16 * hd + 2 * m + 1] = lsum; }
+    }
+    __syncthreads();
+    if (par == 0 && tile_rows) {
+        const float m2 = so[16 * hd + 2 * m], l2 = so[16 * hd + 2 * m + 1];
+        const float mn = fmaxf(mx, m2);
+        const float c1 = mn == -INFINITY ? 1.f : __expf(mx - mn);
+        const float c2 = mn == -INFINITY ? 1.f : __expf(m2 - mn);
+        lsum = lsum * c1 + l2 * c2;
+        mx = mn;
+#pragma unroll
+        for (int dt = 0; dt < ndt; ++dt) {
+            const f32x4 o2 = *reinterpret_cast<const f32x4*>(so + (size_t)m * hd + 16 * dt + 4 * qd);
+            o[dt] = o[dt] * c1 + o2 * c2;
+        }
+        if (r < R && qi_row < a.nq) {
+            const size_t row = (size_t)(b * a.nq + qi_row), head = (size_t)(g * Gq + jq);
+            if (C == 1) {
+                const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+                BF16* op = a.att + (row * a.H + head) * hd;
+#pragma unroll
+                for (int dt = 0; dt < ndt; ++dt)
+                    *reinterpret_cast<u32x2*>(op + 16 * dt + 4 * qd) = pack_bf16x4(o[dt][0] * inv, o[dt][1] * inv, o[dt][2] * inv, o[dt][3] * inv);
+            } else {
+                const size_t rows_all = (size_t)a.B * a.nq;
+                float* po = aa.part_o + (((size_t)c * rows_all + row) * a.H + head) * hd;
+#pragma unroll
+                for (int dt = 0; dt < ndt; ++dt) *reinterpret_cast<f32x4*>(po + 16 * dt + 4 * qd) = o[dt];
+                if (qd == 0) {
+                    float* pm = aa.part_ml + (((size_t)c * rows_all + row) * a.H + head) * 2;
+                    pm[0] = mx;
+                    pm[1] = lsum;
+                }
+            }
+        }
+    }
+}
+
+// adds the key chunks of k_attn_staged in the order c = 0, 1, ..: one thread per (row, head, 4 dims)
+__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml, int C, size_t rows_all,
+                                                    int H, int hd, BF16* __restrict__ att) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t per_row = (size_t)H * hd / 4;
+    if (idx >= rows_all * per_row) return;
+    const size_t row = idx / per_row, rem = idx % per_row;
+    const int head = (int)(rem / (hd / 4)), d4 = (int)(rem % (hd / 4));
+    float mx = -INFINITY, lsum = 0.f;
+    f32x4 o = f32x4{0, 0, 0, 0};
+    for (int c = 0; c < C; ++c) {
+        const size_t rh = ((size_t)c * rows_all + row) * H + head;
+        const float m2 = part_ml[rh * 2], l2 = part_ml[rh * 2 + 1];
+        const f32x4 o2 = *reinterpret_cast<const f32x4*>(part_o + rh * hd + 4 * d4);
+        const float mn = fmaxf(mx, m2);
+        const float c1 = mn == -INFINITY ? 1.f : __expf(mx - mn);
+        const float c2 = mn == -INFINITY ? 1.f : __expf(m2 - mn);
+        lsum = lsum * c1 + l2 * c2;
+        o = o * c1 + o2 * c2;
+        mx = mn;
+    }
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    *reinterpret_cast<u32x2*>(att + (row * H + head) * hd + 4 * d4) = pack_bf16x4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
+}
