@@ -306,3 +306,64 @@ def test_tiled_mfma_kernels(heads):
             outs[tiled] = out
     finally:
         T.tasc_config_set(T.TASC_CFG_TILED_PATH, 1)
+
+
+@pytest.mark.parametrize("shape", ["two_row_passes_long_keys", "one_chunk_many_sequences", "hd128_long_keys"])
+def test_staged_attention_shapes(shape):
+    """The LDS-staged attention at the edges of its launch shapes: more than 64 (row, head) pairs per KV head (two row
+    passes), several key tiles per chunk and chunks without tiles, and so many sequences that every KV head runs as one
+    chunk (no merge kernel); speculative = greedy and logits against the oracle."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    base = W.get_config("cfg1")
+    if shape == "two_row_passes_long_keys":
+        # 14 query heads on 2 KV heads: 7 x 16 prompt rows = 112 pairs per KV head; prompts of up to 700 tokens = 11 key tiles
+        cfg = base.scaled(dtype="bf16", n_layers=2, d_model=128, n_heads=14, n_kv_heads=2, head_dim=64, d_ffn=256, vocab=800,
+                          batch=3, prompt_len=700, gen_len=20, k=9, n_docs=1200, n_max=3)
+        lens, check = [700, 333, 65], [0, 1, 2]
+    elif shape == "one_chunk_many_sequences":
+        cfg = base.scaled(dtype="bf16", n_layers=1, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64, d_ffn=128, vocab=600,
+                          batch=140, prompt_len=70, gen_len=12, k=3, n_docs=1200, n_max=3)
+        lens, check = [70 - (b * 5) % 66 for b in range(140)], [0, 13, 139]
+    else:
+        cfg = base.scaled(dtype="bf16", n_layers=2, d_model=128, n_heads=4, n_kv_heads=1, head_dim=128, d_ffn=256, vocab=800,
+                          batch=2, prompt_len=1100, gen_len=16, k=15, n_docs=1200, n_max=3)
+        lens, check = [1100, 129], [0, 1]
+    rig = Rig(cfg, max_rows=16)
+    rng = np.random.default_rng(23)
+    prompts = [rng.integers(0, cfg.vocab, n).astype(np.int32) for n in lens]
+    rig.prompts = np.concatenate(prompts)
+    rig.prompt_off = np.cumsum([0] + lens).astype(np.int64)
+    print(f"{shape}: batch {cfg.batch}, heads {cfg.n_heads}/{cfg.n_kv_heads} x {cfg.head_dim}, longest prompt {max(lens)}", flush=True)
+    out, st, _ = rig.generate()
+    g_out, g_st, _ = rig.generate(k=0)
+    assert (out == g_out).all(), "speculative output differs from greedy"
+    assert g_st.steps == cfg.gen_len - 1
+    om = OM.OracleModel(cfg, rig.weights)
+    T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+    caches = {}
+    for b in check:
+        c = om.new_cache(rig.max_len)
+        z = om.forward(prompts[b].tolist(), c, last_only=True)
+        c.length = lens[b]
+        caches[b] = c
+        first = T.tasc_session_get_tokens(rig.session, b)[-1]
+        top2 = np.sort(z[0])[-2:]
+        assert first == int(np.argmax(z[0])) or top2[1] - top2[0] < 0.1
+    logits = torch.zeros((cfg.batch, cfg.k + 1, cfg.vocab), dtype=torch.float32, device="cuda")
+    drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+    worst = 0.0
+    for s in range(2):
+        T.tasc_draft(rig.ng, rig.session, rig.params(), drafts)
+        before = {b: T.tasc_session_get_tokens(rig.session, b) for b in check}
+        T.tasc_verify_step(rig.model, rig.session, drafts, cfg.k, None, None, logits)
+        got = logits.cpu().numpy()
+        d = drafts.cpu().numpy()
+        for b in check:
+            z = om.forward([int(before[b][-1])] + d[b].tolist(), caches[b])
+            worst = max(worst, float(np.abs(got[b].astype(np.float64) - z).max()))
+            after = T.tasc_session_get_tokens(rig.session, b)
+            caches[b].length += len(after) - len(before[b])
+    print(f"{shape}: max |logit - oracle| = {worst:.3e}", flush=True)
+    assert worst <= 5e-2
