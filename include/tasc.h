@@ -395,6 +395,12 @@ tasc_status tasc_profile_phases(uint64_t* device_buf, int64_t capacity);
  * counters of the other kernels are scaled. */
 tasc_status tasc_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Attainable bf16 MFMA rate of the device: one workgroup of 8 waves per compute unit issues `iters` x 32
+ * independent v_mfma_f32_32x32x16_bf16 per wave on register operands (no memory traffic in the loop);
+ * *tflops (HOST) = the rate of the second of two launches, timed with HIP events on `stream`.  The
+ * reference beside the published peak for the GEMM kernels' utilisation.  Synchronises the stream. */
+tasc_status tasc_calibration_mfma(int32_t iters, void* stream, double* tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,37 @@
+"""Attainable rates of the device beside the published peaks: a plain copy kernel (HBM) and a register-only MFMA loop.
+
+    python -m paper_2602_24174_amd.calibrate
+
+Prints the copy kernel's rate over 1 GiB (read + write, best of 5) and the bf16 MFMA rate of tasc_calibration_mfma.
+"""
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    import torch
+    import paper_2602_24174_amd as T
+    n = 1 << 30
+    src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream().cuda_stream
+    best = 0.0
+    for _ in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        T.tasc_calibration_copy(dst, src, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    print(f"copy kernel, 1 GiB read + 1 GiB written: {best:.2f} TB/s of HBM traffic (published peak 8 TB/s)")
+    rates = [T.tasc_calibration_mfma(2000, stream) for _ in range(3)]
+    print(f"MFMA loop, v_mfma_f32_32x32x16_bf16 on register operands, 8 waves per compute unit: {max(rates):.0f} TFLOP/s "
+          f"(published dense bf16 peak 2500 TFLOP/s)")
+
+
+if __name__ == "__main__":
+    main()

@@ -66,6 +66,68 @@ __global__ void k_calibration_copy(const uint4* __restrict__ src, uint4* __restr
 }
 }  // namespace
 
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 cal_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float cal_f32x16;
+// 8 independent accumulators of 32 x 32 per wave, operands in registers: nothing but the MFMA pipe is busy
+__global__ __launch_bounds__(512) void k_calibration_mfma(int iters, float* sink) {
+    cal_bf16x8 a[2], b[4];
+    for (int i = 0; i < 2; ++i)
+        for (int e = 0; e < 8; ++e) a[i][e] = (__bf16)(float)((threadIdx.x + i + e) & 7);
+    for (int i = 0; i < 4; ++i)
+        for (int e = 0; e < 8; ++e) b[i][e] = (__bf16)(float)((threadIdx.x * 3 + i + e) & 7);
+    cal_f32x16 acc[2][4];
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int e = 0; e < 16; ++e) s += acc[i][j][e];
+    if (s == -1.0f) sink[0] = s;        // sums of non-negative products: never true, keeps the loop
+}
+}  // namespace
+
+extern "C" tasc_status tasc_calibration_mfma(int32_t iters, void* stream, double* tflops) {
+    TASC_REQUIRE(iters >= 1 && iters <= 100000 && tflops, "calibration_mfma: iters %d outside [1, 100000] or null result", iters);
+    hipStream_t st = (hipStream_t)stream;
+    int dev = 0, cus = 0;
+    TASC_HIP(hipGetDevice(&dev));
+    TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    float* sink = nullptr;
+    TASC_HIP(hipMalloc((void**)&sink, sizeof(float)));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    float ms = 0.f;
+    if (e == hipSuccess) {
+        k_calibration_mfma<<<dim3(cus), dim3(512), 0, st>>>(iters, sink);      // warm-up (clocks, code fetch)
+        e = hipEventRecord(e0, st);
+        k_calibration_mfma<<<dim3(cus), dim3(512), 0, st>>>(iters, sink);
+        if (e == hipSuccess) e = hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(sink);
+    if (e != hipSuccess) {
+        tasc_set_error("calibration_mfma: %s", hipGetErrorString(e));
+        return TASC_EHIP;
+    }
+    // per wave and iteration: 32 MFMAs of 32 x 32 x 16 (2 * 32 * 32 * 16 flop each); 8 waves per workgroup
+    *tflops = (double)cus * 8.0 * iters * 32.0 * 32768.0 / (ms * 1e-3) / 1e12;
+    return TASC_OK;
+}
+
 extern "C" tasc_status tasc_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
     TASC_REQUIRE(dst && src && bytes % 16 == 0 && ((uintptr_t)dst & 15) == 0 && ((uintptr_t)src & 15) == 0,
                  "calibration_copy: buffers must be 16-byte aligned and a multiple of 16 bytes long");
