@@ -146,6 +146,7 @@ bool g_tiled_ready = false;
 // Both reduce every output element over k in the same order, so the choice may depend on the row count.
 #define TILE_SMALL 128, 128, 2, 2
 #define TILE_LARGE 256, 256, 2, 4
+#define TILE_NARROW 64, 128, 1, 4      // few rows and a narrow output: twice the workgroups of the small tile
 constexpr int kLargeTileRows = 384;
 
 template <int EPI>
@@ -154,6 +155,9 @@ tasc_status tiled_attrs() {
                                  TG_LDS_BYTES(128, 128)));
     TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TG_LDS_BYTES(256, 256)));
+    if constexpr (EPI != TEPI_LMHEAD)
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     TG_LDS_BYTES(64, 128)));
     return TASC_OK;
 }
 
@@ -168,6 +172,14 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
         dim3 g((unsigned)(((M + 255) / 256) * ((N + 255) / 256)), (unsigned)slices);
         k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
     } else {
+        const long small_wgs = (long)((M + 127) / 128) * ((N + 127) / 128) * slices;
+        if constexpr (EPI != TEPI_LMHEAD) {
+            if (small_wgs <= 128) {     // half of the compute units idle: halve the tile's width (a workgroup each, still)
+                dim3 g((unsigned)(((M + 127) / 128) * ((N + 63) / 64)), (unsigned)slices);
+                k_gemm_tiled<EPI, TILE_NARROW><<<g, dim3(256), TG_LDS_BYTES(64, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+                return;
+            }
+        }
         dim3 g((unsigned)(((M + 127) / 128) * ((N + 127) / 128)), (unsigned)slices);
         k_gemm_tiled<EPI, TILE_SMALL><<<g, dim3(256), TG_LDS_BYTES(128, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
     }

@@ -120,7 +120,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     // memory for the step after that (activations at ka, weights at kw; steps past the last re-read the last one and
     // are never multiplied).  The LDS stores and the fetches so travel under the step's MFMAs instead of ahead of them.
     // Nothing sits under a condition: a conditional load ends in a register copy at the join, which waits for the data.
-    static_assert(PW == 4 && PA == 4 && TG_BK == 64, "the refill is split in four quarters, one per MFMA k-block");
+    static_assert(PW <= 4 && PA <= 4 && TG_BK == 64, "the refill is split in four quarters, one per MFMA k-block");
     auto step = [&](int buf, StageW& w, StageA& sa_, int ka, int kw) __attribute__((always_inline)) {
         const uint16_t* bw = sW + (size_t)(buf * BN + wn * SN + (lane & 31)) * TG_LD + 8 * (lane >> 5);
         const uint16_t* ba = sA + (size_t)(buf * BM + wm * SM + (lane & 31)) * TG_LD + 8 * (lane >> 5);
@@ -133,10 +133,10 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
             for (int i = 0; i < TI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(bw + (size_t)i * 32 * TG_LD + ks * 16);
 #pragma unroll
             for (int j = 0; j < TJ; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(ba + (size_t)j * 32 * TG_LD + ks * 16);
-            *reinterpret_cast<u32x4*>(dw + (size_t)ks * ROWS_PASS * TG_LD) = w.w[ks];
-            *reinterpret_cast<u32x4*>(da + (size_t)ks * ROWS_PASS * TG_LD) = sa_.a[ks];
-            sa_.a[ks] = *reinterpret_cast<const u32x4*>(abase + aoff[ks] + ka);
-            w.w[ks] = *reinterpret_cast<const u32x4*>(wbase + woff[ks] + kw);
+            if (ks < PW) *reinterpret_cast<u32x4*>(dw + (size_t)ks * ROWS_PASS * TG_LD) = w.w[ks];      // compile-time conditions
+            if (ks < PA) *reinterpret_cast<u32x4*>(da + (size_t)ks * ROWS_PASS * TG_LD) = sa_.a[ks];
+            if (ks < PA) sa_.a[ks] = *reinterpret_cast<const u32x4*>(abase + aoff[ks] + ka);
+            if (ks < PW) w.w[ks] = *reinterpret_cast<const u32x4*>(wbase + woff[ks] + kw);
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
