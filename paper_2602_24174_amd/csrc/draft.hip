@@ -65,6 +65,20 @@ __global__ __launch_bounds__(kThreads) void k_draft(DraftArgs a) {
         if (tid <= TASC_MAX_ORDER) s_found[tid] = 0;
         __syncthreads();
 
+        // ---- corpus source: all orders probed at once, the highest hit wins.  Issued first: the probes' global round trips
+        // then run under the other waves' context scan
+        if (q > 0 && tid < n_max - 1) {
+            const int n = n_max - tid;                 // n - 1 context tokens
+            if (n - 1 <= nsuf && a.ng.ord[n].ctx != nullptr) {
+                u64 lo = 0, hi = 0;
+                for (int i = 0; i < n - 1; ++i) tasc_key_put(lo, hi, i, bits, (u32)s_suf[n - 2 - i]);
+                TascSlot hit;
+                if (probe(a.ng.ord[n].ctx, a.ng.ord[n].ctx_mask, lo, hi, n - 1, hit)) {
+                    s_hit[n] = hit;
+                    s_found[n] = 1;
+                }
+            }
+        }
         // ---- context source: match length of every successor position p (context ends at p - 1)
         int n_ctx = 0, T_ctx = 0;
         if (qb > 0) {
@@ -100,19 +114,6 @@ __global__ __launch_bounds__(kThreads) void k_draft(DraftArgs a) {
         }
         const int m_list = n_ctx ? s_m : 0;
 
-        // ---- corpus source: all orders probed at once, the highest hit wins
-        if (q > 0 && tid < n_max - 1) {
-            const int n = n_max - tid;                 // n - 1 context tokens
-            if (n - 1 <= nsuf && a.ng.ord[n].ctx != nullptr) {
-                u64 lo = 0, hi = 0;
-                for (int i = 0; i < n - 1; ++i) tasc_key_put(lo, hi, i, bits, (u32)s_suf[n - 2 - i]);
-                TascSlot hit;
-                if (probe(a.ng.ord[n].ctx, a.ng.ord[n].ctx_mask, lo, hi, n - 1, hit)) {
-                    s_hit[n] = hit;
-                    s_found[n] = 1;
-                }
-            }
-        }
         __syncthreads();
         if (tid == 0) {
             int nc = 0;
