@@ -296,9 +296,23 @@ struct Cleanup {   // frees temporaries on every exit path
 
 }  // namespace
 
+void tasc_build_cache_free(TascBuildCache* c) {
+    for (int i = 0; i < TASC_BUILD_CACHE_SLOTS; ++i) {
+        if (c->p[i]) (void)hipFree(c->p[i]);
+        c->p[i] = nullptr;
+        c->cap[i] = 0;
+    }
+}
+
 extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* doc_offsets, int64_t n_docs,
                                         int32_t vocab, int32_t n_max, int32_t p_min, tasc_mem where, void* stream,
                                         tasc_ngram** out) {
+    return tasc_ngram_build_cached(tokens, doc_offsets, n_docs, vocab, n_max, p_min, where, stream, nullptr, false, out);
+}
+
+tasc_status tasc_ngram_build_cached(const int32_t* tokens, const int64_t* doc_offsets, int64_t n_docs, int32_t vocab, int32_t n_max,
+                                    int32_t p_min, tasc_mem where, void* stream, TascBuildCache* cache, bool counts_only,
+                                    tasc_ngram** out) {
     TASC_REQUIRE(out != nullptr && doc_offsets != nullptr, "ngram_build: null argument");
     TASC_REQUIRE(n_docs >= 0 && vocab >= 1, "ngram_build: n_docs %lld, vocab %d", (long long)n_docs, vocab);
     TASC_REQUIRE(n_max >= 2 && n_max <= TASC_MAX_ORDER, "ngram_build: n_max %d outside [2, %d]", n_max, TASC_MAX_ORDER);
@@ -321,6 +335,7 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
     memset(ng->slots, 0, sizeof ng->slots);
     memset(&ng->stats, 0, sizeof ng->stats);
     ng->unigram = nullptr;
+    ng->borrowed = cache != nullptr;
     ng->p_min = p_min;
     ng->view.n_max = n_max;
     ng->view.bits = bits;
@@ -332,6 +347,27 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
         ~Guard() { if (p) tasc_ngram_destroy(p); }
     } guard{ng};
 
+    // device buffer for call site `site`: from the cache (grown when too small), else a fresh allocation that is
+    // either temporary (freed on return) or handed to the handle
+    auto get_buf = [&](int site, void** p, size_t bytes, bool temporary) -> tasc_status {
+        bytes = bytes ? bytes : 1;
+        if (cache) {
+            if (cache->cap[site] < bytes) {
+                if (cache->p[site]) TASC_HIP(hipFree(cache->p[site]));
+                cache->p[site] = nullptr;
+                cache->cap[site] = 0;
+                const size_t want = bytes + bytes / 8;
+                TASC_HIP(hipMalloc(&cache->p[site], want));
+                cache->cap[site] = want;
+            }
+            *p = cache->p[site];
+            return TASC_OK;
+        }
+        TASC_HIP(hipMalloc(p, bytes));
+        if (temporary) tmp.ptrs.push_back(*p);
+        return TASC_OK;
+    };
+#define TASC_GET(site, p, bytes, temporary) do { tasc_status _rc = get_buf(site, (void**)(p), bytes, temporary); if (_rc != TASC_OK) return _rc; } while (0)
     hipEvent_t ev0, ev1, evc0, evc1;
     TASC_HIP(hipEventCreate(&ev0)); tmp.evs.push_back(ev0);
     TASC_HIP(hipEventCreate(&ev1)); tmp.evs.push_back(ev1);
@@ -341,15 +377,15 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
     const int32_t* d_tok = tokens;
     if (where == TASC_MEM_HOST && T > 0) {
         void* p;
-        TASC_HIP(hipMalloc(&p, T * sizeof(int32_t))); tmp.ptrs.push_back(p);
+        TASC_GET(0, &p, T * sizeof(int32_t), true);
         TASC_HIP(hipMemcpyAsync(p, tokens, T * sizeof(int32_t), hipMemcpyHostToDevice, st));
         d_tok = (const int32_t*)p;
     }
     TASC_HIP(hipEventRecord(ev0, st));
-    TASC_HIP(hipMalloc((void**)&ng->unigram, (size_t)vocab * sizeof(u32)));
+    TASC_GET(1, &ng->unigram, (size_t)vocab * sizeof(u32), false);
     TASC_HIP(hipMemsetAsync(ng->unigram, 0, (size_t)vocab * sizeof(u32), st));
     u64* d_counters;   // [0] distinct [1] kept [2] contexts [3] unigram best [4] bad-token flag
-    TASC_HIP(hipMalloc((void**)&d_counters, 8 * sizeof(u64))); tmp.ptrs.push_back(d_counters);
+    TASC_GET(2, &d_counters, 8 * sizeof(u64), true);
     TASC_HIP(hipMemsetAsync(d_counters, 0, 8 * sizeof(u64), st));
     u64 h_counters[8];
 
@@ -377,14 +413,14 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
     u64* d_slots = nullptr;
     u64 slots_cap = 0;
     if (windows[2] > 0) {
-        TASC_HIP(hipMalloc((void**)&d_rem, T)); tmp.ptrs.push_back(d_rem);
-        TASC_HIP(hipMalloc((void**)&d_off, (size_t)(n_docs + 1) * sizeof(int64_t))); tmp.ptrs.push_back(d_off);
+        TASC_GET(3, &d_rem, T, true);
+        TASC_GET(4, &d_off, (size_t)(n_docs + 1) * sizeof(int64_t), true);
         TASC_HIP(hipMemcpyAsync(d_off, doc_offsets, (size_t)(n_docs + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
         TASC_HIP(hipMemsetAsync(d_rem, 0xFF, T, st));
         k_mark_doc_tails<<<dim3((unsigned)((n_docs + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(d_off, n_docs, n_max, d_rem);
         TASC_LAUNCH_CHECK();
         slots_cap = pow2_at_least(std::max<u64>(1024, windows[2] + windows[2] / 2));
-        TASC_HIP(hipMalloc((void**)&d_slots, slots_cap * sizeof(u64))); tmp.ptrs.push_back(d_slots);
+        TASC_GET(5, &d_slots, slots_cap * sizeof(u64), true);
     }
 
     float count_ms = 0.f;
@@ -419,13 +455,15 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
         const u64 kept = h_counters[1];
         if (kept == 0) continue;
         const u64 fcap = pow2_at_least(std::max<u64>(64, 2 * kept));
-        TascSlot *full, *ctx;
+        TascSlot *full, *ctx = nullptr;
         CtxRef* ref;
-        TASC_HIP(hipMalloc((void**)&full, fcap * sizeof(TascSlot)));
+        TASC_GET(8 + 3 * n, &full, fcap * sizeof(TascSlot), false);
         ng->slots[n][1] = full;
-        TASC_HIP(hipMalloc((void**)&ctx, fcap * sizeof(TascSlot)));
-        ng->slots[n][0] = ctx;
-        TASC_HIP(hipMalloc((void**)&ref, fcap * sizeof(CtxRef))); tmp.ptrs.push_back(ref);
+        if (!counts_only) {
+            TASC_GET(8 + 3 * n + 1, &ctx, fcap * sizeof(TascSlot), false);
+            ng->slots[n][0] = ctx;
+        }
+        TASC_GET(8 + 3 * n + 2, &ref, fcap * sizeof(CtxRef), true);
         TASC_HIP(hipMemsetAsync(full, 0, fcap * sizeof(TascSlot), st));
         TASC_HIP(hipMemsetAsync(ref, 0, fcap * sizeof(CtxRef), st));
         switch (n) {
@@ -438,15 +476,17 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
             default: launch_keep<8>(d_tok, d_slots, cap, (u32)p_min, bits, full, fcap - 1, ref, fcap - 1, st); break;
         }
         TASC_LAUNCH_CHECK();
-        k_materialize_ctx<<<dim3((unsigned)((fcap + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-            d_tok, ref, fcap, n - 1, bits, ctx, &d_counters[2]);
-        TASC_LAUNCH_CHECK();
+        if (!counts_only) {
+            k_materialize_ctx<<<dim3((unsigned)((fcap + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+                d_tok, ref, fcap, n - 1, bits, ctx, &d_counters[2]);
+            TASC_LAUNCH_CHECK();
+        }
         TASC_HIP(hipMemcpyAsync(h_counters, d_counters, 3 * sizeof(u64), hipMemcpyDeviceToHost, st));
         TASC_HIP(hipStreamSynchronize(st));
         ng->stats.contexts[n] = (int64_t)h_counters[2];
         ng->view.ord[n].ctx = ctx;
         ng->view.ord[n].full = full;
-        ng->view.ord[n].ctx_mask = fcap - 1;
+        ng->view.ord[n].ctx_mask = ctx ? fcap - 1 : 0;
         ng->view.ord[n].full_mask = fcap - 1;
     }
     TASC_HIP(hipEventRecord(ev1, st));
@@ -462,6 +502,10 @@ extern "C" tasc_status tasc_ngram_build(const int32_t* tokens, const int64_t* do
 
 extern "C" void tasc_ngram_destroy(tasc_ngram* ng) {
     if (!ng) return;
+    if (ng->borrowed) {
+        delete ng;
+        return;
+    }
     for (int n = 0; n <= TASC_MAX_ORDER; ++n)
         for (int j = 0; j < 2; ++j)
             if (ng->slots[n][j]) (void)hipFree(ng->slots[n][j]);

@@ -67,7 +67,23 @@ struct tasc_ngram {
     u32* unigram;   // device [vocab]
     int32_t p_min;
     tasc_ngram_stats stats;
+    bool borrowed;  // the device buffers belong to a TascBuildCache: tasc_ngram_destroy frees the handle only
 };
+
+// Device buffers of a table build kept across builds (repeated builds over a shrinking corpus: every call site
+// of the builder has a slot, a buffer is re-allocated only when it is too small).  The owner frees them with
+// tasc_build_cache_free once no handle built from them is in use.
+#define TASC_BUILD_CACHE_SLOTS (8 + 3 * (TASC_MAX_ORDER + 1))
+struct TascBuildCache {
+    void* p[TASC_BUILD_CACHE_SLOTS];
+    size_t cap[TASC_BUILD_CACHE_SLOTS];
+};
+void tasc_build_cache_free(TascBuildCache* c);
+// tasc_ngram_build with the buffers taken from `cache` (nullptr: allocate and free as usual) and, with
+// `counts_only`, without the per-context tables (the n-gram counts of slots[n][1] only)
+tasc_status tasc_ngram_build_cached(const int32_t* tokens, const int64_t* doc_offsets, int64_t n_docs, int32_t vocab, int32_t n_max,
+                                    int32_t p_min, tasc_mem where, void* stream, TascBuildCache* cache, bool counts_only,
+                                    tasc_ngram** out);
 
 __host__ __device__ inline u64 tasc_mix64(u64 x) {
     x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;

@@ -236,13 +236,18 @@ extern "C" tasc_status tasc_tok_enrich(const int32_t* tokens, const int64_t* doc
     std::vector<int64_t> offs(doc_offsets, doc_offsets + n_docs + 1);
     TASC_HIP(hipMemcpyAsync(d_off, offs.data(), (size_t)(n_docs + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
 
+    // the builder's buffers are kept across the merges (the corpus only shrinks, so they are allocated once)
+    struct CacheOwner {
+        TascBuildCache c{};
+        ~CacheOwner() { tasc_build_cache_free(&c); }
+    } build_cache;
     u64 T = T0;
     corpus_len[0] = (int64_t)T;
     int done = 0;
     for (; done < budget; ++done) {
         if (T == 0) break;
         tasc_ngram* ng = nullptr;
-        TOK_TRY(tasc_ngram_build(cur, offs.data(), n_docs, vocab_all, n_max, 1, TASC_MEM_DEVICE, stream, &ng));
+        TOK_TRY(tasc_ngram_build_cached(cur, offs.data(), n_docs, vocab_all, n_max, 1, TASC_MEM_DEVICE, stream, &build_cache.c, true, &ng));
         struct Guard { tasc_ngram* p; ~Guard() { tasc_ngram_destroy(p); } } guard{ng};
         int n_cand = 0;
         for (int n = 2; n <= n_max; ++n) {
