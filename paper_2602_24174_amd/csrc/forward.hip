@@ -255,8 +255,8 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
         return false;
     };
-    int att_chunks = 512 / (s->batch * Hkv);          // two workgroups per compute unit in one round
-    att_chunks = att_chunks < 1 ? 1 : (att_chunks > 8 ? 8 : att_chunks);
+    int att_chunks = 512 / (s->batch * Hkv);          // two workgroups per compute unit in one round,
+    att_chunks = att_chunks < 1 ? 1 : (att_chunks > 4 ? 4 : att_chunks);   // but no more than 4 partial results to merge
     const int rows_pass = 32;
     const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
     {
