@@ -168,7 +168,9 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
     // large tiles need enough of them to fill the chip: narrow outputs stay on the small tile (the k order, and so
     // every row's result, is the same for both shapes)
     const long large_wgs = (long)((M + 255) / 256) * ((N + 255) / 256) * slices;
-    if (M >= kLargeTileRows && large_wgs >= 128) {
+    // ... and a very wide output (the LM head) takes them from 129 rows on: one row tile then reads every weight tile
+    // once, and the activations are re-read per 256 instead of per 128 output features
+    if ((M >= kLargeTileRows && large_wgs >= 128) || (M > 128 && large_wgs >= 512)) {
         dim3 g((unsigned)(((M + 255) / 256) * ((N + 255) / 256)), (unsigned)slices);
         k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
     } else {
