@@ -106,6 +106,26 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // LM head: the rows' bias cursors (a chain of three dependent loads) are fetched before the main loop
+    float lm_base[TJ];
+    int64_t lm_cur[TJ], lm_end[TJ];
+    if (EPI == TEPI_LMHEAD) {
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const int m = m0 + SM * wm + 32 * j + (lane & 31);
+            const int strip = (n0 + SN * wn) / TASC_LM_STRIP;
+            lm_base[j] = 0.f;
+            lm_cur[j] = 0;
+            lm_end[j] = 0;
+            if (m < M && lm.bias.rowptr && strip < lm.n_strips) {
+                const int u = lm.sel_tok[m];
+                lm_base[j] = lm.bias.base[u];
+                const int64_t r0 = lm.bias.rowptr[u];
+                lm_cur[j] = r0 + lm.bias_ptr[(size_t)m * (lm.n_strips + 1) + strip];
+                lm_end[j] = r0 + lm.bias_ptr[(size_t)m * (lm.n_strips + 1) + strip + 1];
+            }
+        }
+    }
     int kt_begin = 0, nk = K / TG_BK;
     if (EPI == TEPI_PARTIAL) {
         const int per = (nk + gridDim.y - 1) / gridDim.y;
@@ -176,32 +196,47 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
         static_assert(SN <= TASC_LM_STRIP, "one strip per wave row at most");
         __shared__ float s_bv[WN][BM];
         __shared__ int32_t s_bi[WN][BM];
+        // The seen successors of a row inside the wave's span get their own bias instead of `base`.  A row can have many
+        // of them, and which accumulator element holds a given feature is a lane-and-register question, so the wave
+        // scatters the differences (bias - base) of its 32 rows into a [32][SN] patch in LDS (the two lanes of a row
+        // take alternate groups of 16 entries of the row's list; no load depends on another's value) and every lane
+        // then adds the patch elements of its registers.  The tile buffers are free after the loop's last barrier; LDS
+        // serves a wave's accesses in program order.
+        constexpr int LDP = SN + 1;
+        static_assert((size_t)WN * WM * 32 * LDP * 4 <= TG_LDS_BYTES(BN, BM), "bias patches fit the tile buffers");
+        float* patch = reinterpret_cast<float*>(lds) + wave * (32 * LDP);
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
             const int ml = SM * wm + 32 * j + (lane & 31), m = m0 + ml;
             float best = -INFINITY;
             int32_t best_i = 0x7FFFFFFF;
-            if (m < M) {
-                const int strip = (n0 + SN * wn) / TASC_LM_STRIP;
-                float base = 0.f;
-                if (lm.bias.rowptr && strip < lm.n_strips) {
-                    const int u = lm.sel_tok[m];
-                    base = lm.bias.base[u];
-                    const int64_t r0 = lm.bias.rowptr[u];
-                    const int64_t bp = r0 + lm.bias_ptr[(size_t)m * (lm.n_strips + 1) + strip];
-                    const int64_t be = r0 + lm.bias_ptr[(size_t)m * (lm.n_strips + 1) + strip + 1];
-                    // the few seen successors of this row inside the strip: replace `base` by their own bias
-                    for (int64_t p = bp; p < be; ++p) {
-                        const int nl = lm.bias.col[p] - n0 - SN * wn;        // row within this wave's span
-                        if (nl < 0 || nl >= SN) continue;
-                        const float dv = lm.bias.val[p] - base;
+            const float base = lm_base[j];
+            if (lm.bias.rowptr) {
+                for (int q = lane; q < 32 * LDP; q += 64) patch[q] = 0.f;
+                __builtin_amdgcn_wave_barrier();
+                const int lo = n0 + SN * wn;
+                const int64_t be = lm_end[j];
+                for (int64_t p0 = lm_cur[j] + 16 * (lane >> 5); p0 < be; p0 += 32) {
+                    int nl[16];
+                    float bv[16];
 #pragma unroll
-                        for (int i = 0; i < TI; ++i)
-#pragma unroll
-                            for (int e = 0; e < 16; ++e)
-                                if (32 * i + tile_row(e, lane) == nl) acc[i][j][e] += dv;
+                    for (int q = 0; q < 16; ++q) {           // 32 loads in flight per lane before the first use
+                        const int64_t p = p0 + q < be ? p0 + q : be - 1;
+                        nl[q] = lm.bias.col[p] - lo;
+                        bv[q] = lm.bias.val[p];
                     }
+#pragma unroll
+                    for (int q = 0; q < 16; ++q)
+                        if (p0 + q < be && nl[q] >= 0 && nl[q] < SN) patch[(lane & 31) * LDP + nl[q]] = bv[q] - base;
                 }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int i = 0; i < TI; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] += patch[(lane & 31) * LDP + 32 * i + tile_row(e, lane)];
+                __builtin_amdgcn_wave_barrier();
+            }
+            if (m < M) {
 #pragma unroll
                 for (int i = 0; i < TI; ++i) {
 #pragma unroll
