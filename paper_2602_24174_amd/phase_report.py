@@ -2,8 +2,7 @@
 
     python -m paper_2602_24174_amd.phase_report [--config cfg2] [--grid G] [--layer-wgs N] [--layer-stride S]
 
-Builds the named workload with a reduced corpus (2,000 outputs: the tables do not matter for the forward's
-timing), prefills, runs a few warm verify steps, then one verify step with the per-phase wall-clock stamps
+Builds the named workload (--docs N shrinks the corpus, and with it the LM-head bias table), prefills, runs a few warm verify steps, then one verify step with the per-phase wall-clock stamps
 on, and prints per layer-phase medians: the longest workgroup's work, the span from the first begin to the
 last end, and the barrier gap to the next phase.
 """
@@ -26,13 +25,16 @@ def main():
     ap.add_argument("--layer-stride", type=int, default=0)
     ap.add_argument("--max-rows", type=int, default=16)
     ap.add_argument("--workers", type=int, default=0, help="computing members of the layer group in XCD-local mode (0 = half)")
+    ap.add_argument("--docs", type=int, default=0, help="corpus size (0 = the configuration's; it sets the size of the LM-head bias table)")
     ap.add_argument("--agent-barriers", action="store_true", help="agent-scope barriers only (no XCD-local mode)")
     args = ap.parse_args()
     import torch
     import workload as W
     import paper_2602_24174_amd as T
 
-    cfg = W.get_config(args.config).scaled(n_docs=2000)
+    cfg = W.get_config(args.config)
+    if args.docs:
+        cfg = cfg.scaled(n_docs=args.docs)
     if cfg.batch * args.max_rows > 16:
         sys.exit("the persistent kernel only serves sessions with batch * max_rows <= 16")
     corpus = W.make_corpus(cfg)
