@@ -838,6 +838,17 @@ __device__ __forceinline__ void phase_lmhead(const SmallArgs& a, int wg, int nwg
         float best = -INFINITY;
         int32_t best_i = 0x7FFFFFFF;
         if (own) {
+            if (has_bias) {
+                // the lane's first feature inside the row's sorted list: a binary search, not a walk from the strip's start
+                // (a frequent token has tens of seen successors per strip, and every step is a dependent load)
+                const int c0 = v0 + 4 * qd;
+                int64_t lo = bp, hi = be;
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if (b_col[mid] < c0) lo = mid + 1; else hi = mid;
+                }
+                bp = lo;
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int c = v0 + 4 * qd + u;
