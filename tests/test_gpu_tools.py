@@ -1,0 +1,34 @@
+"""Measurement helpers of the library on the GPU: the calibration kernels run, copy correctly and report sane rates."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def test_calibration_copy_and_mfma():
+    import torch
+    import paper_2602_24174_amd as T
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    T.tasc_calibration_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    rate = T.tasc_calibration_mfma(200)
+    print(f"MFMA loop: {rate:.0f} TFLOP/s", flush=True)
+    assert 200.0 < rate < 2600.0            # above any vector-ALU rate, below the published dense bf16 peak
+    with pytest.raises(T.TascError):
+        T.tasc_calibration_mfma(0)
+    with pytest.raises(T.TascError):
+        T.tasc_calibration_copy(dst[1:], src[1:])     # 4-byte offset: not 16-byte aligned
+
+
+def test_position_rates_from_a_real_run():
+    """The sweep helper on a live generate: rates are non-increasing in the position and consistent with the mean."""
+    import workload as W
+    from paper_2602_24174_amd.acceptance_sweeps import SweepRig
+    cfg = W.get_config("cfg1").scaled(gen_len=40)
+    rig = SweepRig(cfg)
+    r = rig.run(k=6, lam=0.5)
+    assert r["equals_greedy"]
+    assert all(a >= b for a, b in zip(r["rate"], r["rate"][1:]))
+    assert abs(sum(r["rate"]) - r["mean_accept"]) < 1e-9
+    assert sum(r["hist"]) == r["steps"] * cfg.batch
