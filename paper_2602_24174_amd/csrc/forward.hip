@@ -147,6 +147,7 @@ bool g_tiled_ready = false;
 #define TILE_SMALL 128, 128, 2, 2
 #define TILE_LARGE 256, 256, 2, 4
 #define TILE_NARROW 64, 128, 1, 4      // few rows and a narrow output: twice the workgroups of the small tile
+#define TILE_MID 256, 192, 4, 2        // 192 rows per tile where that leaves fewer padded rows than 256 (576 = 3 x 192)
 constexpr int kLargeTileRows = 384;
 
 template <int EPI>
@@ -155,6 +156,8 @@ tasc_status tiled_attrs() {
                                  TG_LDS_BYTES(128, 128)));
     TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  TG_LDS_BYTES(256, 256)));
+    TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_MID>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 TG_LDS_BYTES(256, 192)));
     if constexpr (EPI != TEPI_LMHEAD)
         TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_tiled<EPI, TILE_NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      TG_LDS_BYTES(64, 128)));
@@ -171,7 +174,15 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
     // ... and a very wide output (the LM head) takes them from 129 rows on: one row tile then reads every weight tile
     // once, and the activations are re-read per 256 instead of per 128 output features
     if ((M >= kLargeTileRows && large_wgs >= 128) || (M > 128 && large_wgs >= 512)) {
-        dim3 g((unsigned)(((M + 255) / 256) * ((N + 255) / 256)), (unsigned)slices);
+        // 192-row tiles where they cover the rows with less padding and no more tiles (the tile shape never changes a
+        // row's result)
+        const int mt256 = (M + 255) / 256, mt192 = (M + 191) / 192;
+        if (EPI != TEPI_LMHEAD && mt192 <= mt256 && mt192 * 192 < mt256 * 256) {   // (the LM head's bias walk prefers 128-wide waves)
+            dim3 g((unsigned)(mt192 * ((N + 255) / 256)), (unsigned)slices);
+            k_gemm_tiled<EPI, TILE_MID><<<g, dim3(512), TG_LDS_BYTES(256, 192), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+            return;
+        }
+        dim3 g((unsigned)(mt256 * ((N + 255) / 256)), (unsigned)slices);
         k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
     } else {
         const long small_wgs = (long)((M + 127) / 128) * ((N + 127) / 128) * slices;
