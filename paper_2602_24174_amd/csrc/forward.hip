@@ -283,7 +283,8 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         BF16* kv_layer = (BF16*)s->kv_pool + (size_t)l * s->kv_layer_stride;
         if (!h_ready) {
             PROF(TASC_KC_NORM);
-            k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (BF16*)d.h);
+            if (D <= RRN_MAX_D) k_rmsnorm_row<<<dim3(M), dim3(256), 0, st>>>(d.x, w.g1, D, c.rms_eps, (BF16*)d.h);
+            else k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (BF16*)d.h);
         }
         const int ks_qkv = slices(nqkv, D);
         {
@@ -326,7 +327,8 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         }
         if (!normed) {
             PROF(TASC_KC_NORM);
-            k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (BF16*)d.h);
+            if (D <= RRN_MAX_D) k_rmsnorm_row<<<dim3(M), dim3(256), 0, st>>>(d.x, w.g2, D, c.rms_eps, (BF16*)d.h);
+            else k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (BF16*)d.h);
         }
         {
             PROF(TASC_KC_GEMM_GU);

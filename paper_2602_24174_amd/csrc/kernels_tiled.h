@@ -390,6 +390,39 @@ __global__ __launch_bounds__(256) void k_reduce_resid_norm(const float* __restri
     }
 }
 
+// RMSNorm of whole rows for the tiled path: k_reduce_resid_norm's scheme without the slices (one workgroup of 256
+// threads per row, the row in registers between the sum of squares and the scaling).  d <= 2048, d % 4 == 0.
+__global__ __launch_bounds__(256) void k_rmsnorm_row(const float* __restrict__ x, const float* __restrict__ g, int d, float eps,
+                                                     BF16* __restrict__ h) {
+    const int r = blockIdx.x, t = threadIdx.x;
+    const float* xr = x + (size_t)r * d;
+    f32x4 v[2], gg[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int k = 4 * (t + 256 * u);
+        const int kc = k < d ? k : 0;                                // unconditional loads; the clamped ones are unused
+        v[u] = *reinterpret_cast<const f32x4*>(xr + kc);
+        gg[u] = *reinterpret_cast<const f32x4*>(g + kc);
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (4 * (t + 256 * u) < d) ss += v[u][0] * v[u][0] + v[u][1] * v[u][1] + v[u][2] * v[u][2] + v[u][3] * v[u][3];
+    __shared__ float s_ss[4];
+    ss = wave_sum(ss);
+    if ((t & 63) == 0) s_ss[t >> 6] = ss;
+    __syncthreads();
+    ss = ((s_ss[0] + s_ss[1]) + s_ss[2]) + s_ss[3];
+    const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int k = 4 * (t + 256 * u);
+        if (k < d)
+            *reinterpret_cast<u32x2*>(h + (size_t)r * d + k) =
+                pack_bf16x4(v[u][0] * rinv * gg[u][0], v[u][1] * rinv * gg[u][1], v[u][2] * rinv * gg[u][2], v[u][3] * rinv * gg[u][3]);
+    }
+}
+
 // cursor table of the LM-head bias (see LmEpi): one thread per (row, strip boundary)
 __global__ void k_bias_ptr(BiasCsr bias, const int32_t* __restrict__ sel_tok, int n_sel, int n_strips, int32_t* __restrict__ out) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
