@@ -89,3 +89,51 @@ def test_full_size_config(name, max_rows, n_steps, sample):
         cache.length += len(T.tasc_session_get_tokens(rig.session, 0)) - len(before)
     print(f"{name}: max |logit - oracle| over {n_steps} verify steps = {worst:.3e}", flush=True)
     assert worst <= 5e-2
+
+
+def test_cfg4_model_at_its_launch_shapes():
+    """The 1.5B-class model with config 4's batch and draft length (576 rows per verify step: the 256 x 192 GEMM tiles,
+    head_dim 128 attention in 4 key chunks) on short prompts and a small corpus, so that the oracle can follow a
+    sequence: speculative == greedy on all 64 sequences, accept lengths consistent with the GPU's own drafts and argmax
+    ids, and the logits of one sequence's prompt forward and first verify step against the oracle."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig, split_trace
+    cfg = W.get_config("cfg4").scaled(n_docs=3000, prompt_len=48, gen_len=20)
+    print("cfg4 model: building inputs", flush=True)
+    rig = Rig(cfg, max_rows=64)
+    out, st, tr = rig.generate(trace_steps=cfg.gen_len)
+    g_out, g_st, _ = rig.generate(k=0)
+    assert (out == g_out).all(), "speculative output differs from the GPU's own greedy decode"
+    assert g_st.steps == cfg.gen_len - 1
+    n_before, drafts, amax, acc = split_trace(tr, cfg.k)
+    for s in range(tr.shape[0]):
+        for b in range(cfg.batch):
+            if acc[s, b] >= 0:
+                assert acc[s, b] == OM.accept_length(drafts[s, b].tolist(), amax[s, b].tolist())
+    print(f"steps {st.steps} vs greedy {g_st.steps}; accepted {st.accepted}/{st.proposed}", flush=True)
+    om = OM.OracleModel(cfg, rig.weights)
+    b = 5
+    T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+    prompt = rig.prompts[rig.prompt_off[b]:rig.prompt_off[b + 1]].tolist()
+    cache = om.new_cache(rig.max_len)
+    z = om.forward(prompt, cache, last_only=True)
+    cache.length = len(prompt)
+    first = int(T.tasc_session_get_tokens(rig.session, b)[-1])
+    top2 = np.sort(z[0])[-2:]
+    assert first == int(np.argmax(z[0])) or top2[1] - top2[0] < 0.1
+    logits = torch.zeros((cfg.batch, cfg.k + 1, cfg.vocab), dtype=torch.float32, device="cuda")
+    drafts_d = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+    T.tasc_draft(rig.ng, rig.session, rig.params(), drafts_d)
+    before = T.tasc_session_get_tokens(rig.session, b)
+    T.tasc_verify_step(rig.model, rig.session, drafts_d, cfg.k, None, None, logits)
+    got = logits[b].cpu().numpy().astype(np.float64)
+    z = om.forward([int(before[-1])] + drafts_d[b].cpu().numpy().tolist(), cache)
+    worst = float(np.abs(got - z).max())
+    rms = float(np.sqrt(((got - z) ** 2).mean()))
+    print(f"cfg4 model: max |logit - oracle| = {worst:.3e}, rms {rms:.3e}", flush=True)
+    # 28 layers of width 1536 with bf16 activations between the kernels: the rounding of the GEMM inputs alone gives an
+    # rms error of 1.2e-2 - 1.3e-2 on logits of standard deviation 1.0 in BOTH kernel families (type-generic and MFMA;
+    # they differ from each other by as much), and the largest of 1.4 M logits then lies near 5.4 sigma = 0.07.  The 5e-2
+    # bound of the smaller configurations is therefore checked here on the rms, and the maximum against 1e-1.
+    assert rms <= 2e-2 and worst <= 1e-1
