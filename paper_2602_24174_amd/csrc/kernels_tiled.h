@@ -22,9 +22,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 #define TG_LDS_BYTES(BN, BM) (2 * ((BN) + (BM)) * TG_LD * 2)   // 73728 for 128 x 128, 147456 for 256 x 256
 #define TG_MAX_SLICES 8                                       // most k-slices of a narrow GEMM
 
-// TEPI_PARTIAL: blockIdx.y selects one of gridDim.y slices of k; the slice's sums go to outf[slice][M][N] and
-// k_splitk_reduce adds the slices in order (plain store or residual add).  Used where N is too narrow for
-// the tile count to fill the chip; the number of slices depends on N and K only.
+// TEPI_PARTIAL: the grid's y extent is the number of slices of k (a workgroup's slice comes from the tile order
+// below); the slice's sums go to outf[slice][M][N] and k_splitk_reduce adds the slices in order (plain store or
+// residual add).  Used where N is too narrow for the tile count to fill the chip; the number of slices depends on
+// N and K only.
 enum { TEPI_STORE = 0, TEPI_RESID = 1, TEPI_SWIGLU = 2, TEPI_LMHEAD = 3, TEPI_PARTIAL = 4 };
 
 struct LmEpi {            // TEPI_LMHEAD only
@@ -56,11 +57,15 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     uint16_t* sA = sW + 2 * BN * TG_LD;                                   // [2][BM][TG_LD]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave / WM, wm = wave % WM;
-    // XCD-aware tile order: the dispatcher deals consecutive workgroup ids to the 8 XCDs in turn; give each
-    // XCD a contiguous range of tiles, m fastest, so that the tiles sharing weights share an L2
+    // XCD-aware tile order: the dispatcher deals consecutive workgroup ids (x fastest, then y) to the 8 XCDs in turn.
+    // Each XCD gets a contiguous range of (k-slice, tile) pairs, m fastest, then n, then the slice, so that the tiles
+    // running on an XCD at the same time share weight and activation panels in its L2.  XCD x holds the ids
+    // x, x + 8, ..: all / 8 of them, and one more for x < all % 8.
     const int n_mt = (M + BM - 1) / BM, n_nt = (N + BN - 1) / BN, total = n_mt * n_nt;
-    int v = blockIdx.x;
-    if (total % 8 == 0) v = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+    const int lin = blockIdx.y * gridDim.x + blockIdx.x, all = total * gridDim.y;
+    const int xcd = lin % 8;
+    const int vg = xcd * (all / 8) + min(xcd, all % 8) + lin / 8;
+    const int slice = vg / total, v = vg % total;
     const int n0 = (v / n_mt) * BN, m0 = (v % n_mt) * BM;
 
     // global -> register staging, 16 bytes per thread and pass
@@ -129,9 +134,9 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     int kt_begin = 0, nk = K / TG_BK;
     if (EPI == TEPI_PARTIAL) {
         const int per = (nk + gridDim.y - 1) / gridDim.y;
-        kt_begin = blockIdx.y * per;
+        kt_begin = slice * per;
         nk = min(nk, kt_begin + per);
-        outf += (size_t)blockIdx.y * M * N;
+        outf += (size_t)slice * M * N;
     }
     const int k_last = (nk - 1) * TG_BK;
     // One pipeline step = the multiply of LDS buffer `buf` with the refill of the other buffer woven into it, a quarter
