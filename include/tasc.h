@@ -401,6 +401,14 @@ tasc_status tasc_calibration_copy(void* dst, const void* src, size_t bytes, void
  * reference beside the published peak for the GEMM kernels' utilisation.  Synchronises the stream. */
 tasc_status tasc_calibration_mfma(int32_t iters, void* stream, double* tflops);
 
+/* Attainable read rate of the device for a stream of independent 16-byte loads: one workgroup of 512 threads per
+ * compute unit takes 64 KB blocks of src (DEVICE pointer, 16-byte aligned, bytes a multiple of 65536) round-robin,
+ * 8 loads in flight per lane, `passes` times over the buffer, and stores nothing.  *gbps (HOST) = bytes read / time of
+ * the second of two launches (HIP events on `stream`).  A buffer of a few MB stays in the L2 of every XCD and gives
+ * the L2-to-compute-unit rate, one beyond the memory-side cache (> 256 MB) the HBM read rate: the references beside
+ * the published 8 TB/s for the kernels that stream weights and the KV cache.  Synchronises the stream. */
+tasc_status tasc_calibration_read(const void* src, size_t bytes, int32_t passes, void* stream, double* gbps);
+
 #ifdef __cplusplus
 }
 #endif

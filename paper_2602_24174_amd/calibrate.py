@@ -1,8 +1,10 @@
-"""Attainable rates of the device beside the published peaks: a plain copy kernel (HBM) and a register-only MFMA loop.
+"""Attainable rates of the device beside the published peaks: a plain copy kernel and a read stream (HBM, L2) and a
+register-only MFMA loop.
 
     python -m paper_2602_24174_amd.calibrate
 
-Prints the copy kernel's rate over 1 GiB (read + write, best of 5) and the bf16 MFMA rate of tasc_calibration_mfma.
+Prints the copy kernel's rate over 1 GiB (read + write, best of 5), the read rates of tasc_calibration_read over 1 GiB
+(HBM), 128 MiB (memory-side cache) and 2 MiB (the L2 of every XCD), and the bf16 MFMA rate of tasc_calibration_mfma.
 """
 import os
 import sys
@@ -28,6 +30,10 @@ def main():
         torch.cuda.synchronize()
         best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e12)
     print(f"copy kernel, 1 GiB read + 1 GiB written: {best:.2f} TB/s of HBM traffic (published peak 8 TB/s)")
+    for label, nbytes, passes in (("1 GiB (HBM)", 1 << 30, 8), ("128 MiB (memory-side cache)", 128 << 20, 64), ("2 MiB (L2 of every XCD)", 2 << 20, 4096)):
+        rate = max(T.tasc_calibration_read(src[:nbytes], passes, stream) for _ in range(3))
+        print(f"read stream over {label}, 8 independent 16-byte loads per lane: {rate / 1e3:.2f} TB/s "
+              f"({rate / torch.cuda.get_device_properties(0).multi_processor_count:.0f} GB/s per compute unit)")
     rates = [T.tasc_calibration_mfma(2000, stream) for _ in range(3)]
     print(f"MFMA loop, v_mfma_f32_32x32x16_bf16 on register operands, 8 waves per compute unit: {max(rates):.0f} TFLOP/s "
           f"(published dense bf16 peak 2500 TFLOP/s)")

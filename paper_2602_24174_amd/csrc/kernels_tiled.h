@@ -662,8 +662,9 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_attn_tiled(AttnArgs a) {
 // launch's row count, and a tile past a row's position contributes exactly nothing to that row.  The 8 waves load a tile
 // (keys [64][hd], values [hd][64]) from the pages into registers while the previous one is multiplied out of LDS, so the
 // tile is read once for all 64 rows.  Wave w multiplies row tile w % 4 (16 rows) by the 32 keys w / 4 of the tile
-// (S^T = K Q^T, O^T = V^T P^T with 16x16x32 MFMAs, as in the small-batch kernel); the two key halves of a row tile are
-// merged through LDS at the end.  C == 1: the result goes to `att`; C > 1: unnormalised sums, running maxima and
+// (S^T = K Q^T, O^T = V^T P^T with 16x16x32 MFMAs; the key rows are parked in the order that leaves a lane with 8
+// consecutive keys, so the values come as one 16-byte LDS read per lane and tile of 16 dims); the two key halves of a
+// row tile are merged through LDS at the end.  C == 1: the result goes to `att`; C > 1: unnormalised sums, running maxima and
 // denominators go to part_o / part_ml for k_attn_merge, which adds the chunks in the order c = 0, 1, ...
 struct AttnStagedArgs {
     AttnArgs a;
@@ -748,7 +749,11 @@ __global__ __launch_bounds__(SMALL_THREADS) __attribute__((amdgpu_waves_per_eu(4
         for (int u = 0; u < LPT; ++u) {
             const int q = tid + SMALL_THREADS * u;
             const int key = q / (hd / 8), dch = q % (hd / 8);
-            *reinterpret_cast<u32x4*>(sK + (size_t)(buf * 64 + key) * KLD + 8 * dch) = rk[u];
+            // LDS row of a key: within its half of 32, keys 8 j .. 8 j + 3 go to rows 4 j .. 4 j + 3 and keys 8 j + 4 .. 8 j + 7
+            // to rows 16 + 4 j ..: the two S^T tiles of a wave then leave lane group j with the scores of keys 8 j .. 8 j + 7,
+            // the order in which the second product takes its k index, and a lane's 8 values are one 16-byte LDS read
+            const int krow = (key & 32) + 16 * ((key >> 2) & 1) + 4 * ((key >> 3) & 3) + (key & 3);
+            *reinterpret_cast<u32x4*>(sK + (size_t)(buf * 64 + krow) * KLD + 8 * dch) = rk[u];
             const int vp = q / (2 * hd), dim = (q % (2 * hd)) / 2, half = q % 2;
             *reinterpret_cast<u32x4*>(sV + (size_t)(buf * hd + dim) * VLD + TASC_KV_BLOCK * vp + 8 * half) = rv[u];
         }
@@ -756,7 +761,7 @@ __global__ __launch_bounds__(SMALL_THREADS) __attribute__((amdgpu_waves_per_eu(4
     auto multiply = [&](int buf, int t) __attribute__((always_inline)) {
         const int key0 = 64 * t + 32 * par;
         const uint16_t* kb = sK + (size_t)(buf * 64 + 32 * par + m) * KLD + 8 * qd;
-        const uint16_t* vb = sV + (size_t)(buf * hd + m) * VLD + 32 * par + 4 * qd;
+        const uint16_t* vb = sV + (size_t)(buf * hd + m) * VLD + 32 * par + 8 * qd;
         f32x4 s0 = f32x4{0, 0, 0, 0}, s1 = f32x4{0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
@@ -769,7 +774,7 @@ __global__ __launch_bounds__(SMALL_THREADS) __attribute__((amdgpu_waves_per_eu(4
         float tmax = -INFINITY;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int key = key0 + (u < 4 ? 4 * qd + u : 16 + 4 * qd + (u - 4));
+            const int key = key0 + 8 * qd + u;                       // see the row order in park()
             const float sc = (u < 4 ? s0[u] : s1[u - 4]) * a.scale;
             sv[u] = (key <= qi) ? sc : -INFINITY;
             tmax = fmaxf(tmax, sv[u]);
@@ -795,10 +800,9 @@ __global__ __launch_bounds__(SMALL_THREADS) __attribute__((amdgpu_waves_per_eu(4
         mx = m_new;
 #pragma unroll
         for (int dt = 0; dt < ndt; ++dt) {
-            const u32x2 h0 = *reinterpret_cast<const u32x2*>(vb + (size_t)16 * dt * VLD);
-            const u32x2 h1 = *reinterpret_cast<const u32x2*>(vb + (size_t)16 * dt * VLD + 16);
+            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vb + (size_t)16 * dt * VLD);
             o[dt] *= corr;
-            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(h0[0], h0[1], h1[0], h1[1]), pk, o[dt], 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pk, o[dt], 0, 0, 0);
         }
     };
     if (n_my > 0) {

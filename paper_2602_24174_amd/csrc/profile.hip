@@ -128,6 +128,60 @@ extern "C" tasc_status tasc_calibration_mfma(int32_t iters, void* stream, double
     return TASC_OK;
 }
 
+namespace {
+typedef unsigned int cal_u32x4 __attribute__((ext_vector_type(4)));
+// read stream: a workgroup of 512 threads takes blocks of 64 KB, 8 independent 16-byte loads per lane, nothing stored
+__global__ __launch_bounds__(512) void k_calibration_read(const cal_u32x4* __restrict__ src, size_t n_blocks, size_t steps, unsigned* sink) {
+    cal_u32x4 acc = {0, 0, 0, 0};
+    for (size_t it = 0; it < steps; ++it) {
+        const size_t blk = (it * gridDim.x + blockIdx.x) % n_blocks;
+        const cal_u32x4* p = src + blk * 4096 + threadIdx.x;
+        cal_u32x4 r[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r[q] = p[q * 512];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc ^= r[q];
+    }
+    if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u && acc[2] == 0x94d049bbu && acc[3] == 0xbf58476du) sink[0] = acc[0];   // keeps the loads
+}
+}  // namespace
+
+extern "C" tasc_status tasc_calibration_read(const void* src, size_t bytes, int32_t passes, void* stream, double* gbps) {
+    TASC_REQUIRE(src && gbps && bytes >= 65536 && bytes % 65536 == 0 && ((uintptr_t)src & 15) == 0 && passes >= 1 && passes <= 1000000,
+                 "calibration_read: 16-byte aligned buffer of a multiple of 64 KB and 1 .. 1000000 passes needed");
+    hipStream_t st = (hipStream_t)stream;
+    int dev = 0, cus = 0;
+    TASC_HIP(hipGetDevice(&dev));
+    TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const size_t n_blocks = bytes / 65536;
+    const unsigned wgs = (unsigned)cus;
+    const size_t steps = (n_blocks * (size_t)passes + wgs - 1) / wgs;
+    TASC_REQUIRE(steps <= ((size_t)1 << 26), "calibration_read: %zu blocks x %d passes is too much work for one launch", n_blocks, passes);
+    unsigned* sink = nullptr;
+    TASC_HIP(hipMalloc((void**)&sink, sizeof(unsigned)));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    float ms = 0.f;
+    if (e == hipSuccess) {
+        k_calibration_read<<<dim3(wgs), dim3(512), 0, st>>>((const cal_u32x4*)src, n_blocks, steps < 64 ? steps : 64, sink);   // warm-up
+        e = hipEventRecord(e0, st);
+        k_calibration_read<<<dim3(wgs), dim3(512), 0, st>>>((const cal_u32x4*)src, n_blocks, steps, sink);
+        if (e == hipSuccess) e = hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(sink);
+    if (e != hipSuccess) {
+        tasc_set_error("calibration_read: %s", hipGetErrorString(e));
+        return TASC_EHIP;
+    }
+    *gbps = (double)wgs * (double)steps * 65536.0 / (ms * 1e-3) / 1e9;
+    return TASC_OK;
+}
+
 extern "C" tasc_status tasc_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
     TASC_REQUIRE(dst && src && bytes % 16 == 0 && ((uintptr_t)dst & 15) == 0 && ((uintptr_t)src & 15) == 0,
                  "calibration_copy: buffers must be 16-byte aligned and a multiple of 16 bytes long");

@@ -4,7 +4,7 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 
-def test_calibration_copy_and_mfma():
+def test_calibration_copy_read_and_mfma():
     import torch
     import paper_2602_24174_amd as T
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
@@ -15,6 +15,12 @@ def test_calibration_copy_and_mfma():
     rate = T.tasc_calibration_mfma(200)
     print(f"MFMA loop: {rate:.0f} TFLOP/s", flush=True)
     assert 200.0 < rate < 2600.0            # above any vector-ALU rate, below the published dense bf16 peak
+    buf = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    small, large = T.tasc_calibration_read(buf[:2 << 20], 512), T.tasc_calibration_read(buf, 8)
+    print(f"read stream: 2 MiB {small:.0f} GB/s, 64 MiB {large:.0f} GB/s", flush=True)
+    assert 500.0 < large < 40000.0 and small > large      # the L2-resident stream is the faster one
+    with pytest.raises(T.TascError):
+        T.tasc_calibration_read(buf[:1000], 1)             # not a multiple of 64 KB
     with pytest.raises(T.TascError):
         T.tasc_calibration_mfma(0)
     with pytest.raises(T.TascError):
