@@ -132,6 +132,22 @@ typedef struct {
 tasc_status tasc_ngram_entropy(const tasc_ngram* ng, int32_t order, int32_t coverage_ppm,
                                tasc_table_entropy* out, void* stream);
 
+/*
+ * tasc_ngram_entropy for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same kernels in the same order, with their scratch (the
+ * per-workgroup partial sums, the two select histograms, the select state: 37 KB) in a fixed array inside the
+ * library instead of a hipMalloc'ed buffer.  Calls no hipMalloc / hipFree and does not synchronise: it only
+ * enqueues kernels on `stream` (the scratch is cleared by a kernel, not a memset).
+ *   out_device  DEVICE tasc_table_entropy, written by the last kernel; valid once `stream` has been synchronised.
+ * Every call on one device shares that device's array: calls that overlap on one device (different streams)
+ * race; calls on one stream are ordered and independent (each clears the scratch first).
+ * Limit: tables of at most TASC_ENTROPY_NOALLOC_MAX_SLOTS hash slots (order 1: vocabulary entries); beyond it
+ * TASC_ENOMEM and nothing is enqueued.  Other errors as tasc_ngram_entropy.
+ */
+#define TASC_ENTROPY_NOALLOC_MAX_SLOTS (1ull << 32)
+tasc_status tasc_ngram_entropy_noalloc(const tasc_ngram* ng, int32_t order, int32_t coverage_ppm,
+                                       tasc_table_entropy* out_device, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Target model.  The paper uses the target as a black box; the architecture (pre-norm RMSNorm,
  * RoPE with rotate-half pairing, grouped-query attention, SwiGLU, untied LM head, sparse additive

@@ -19,7 +19,7 @@ TASC_MAX_ORDER, TASC_MAX_K = 8, 15
 
 EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
-    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_tok_enrich", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
+    "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_ngram_entropy_noalloc", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_tok_enrich", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
     "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read",
 ]
@@ -99,6 +99,7 @@ def lib():
         L.tasc_model_bigram.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tasc_ngram_from_bigram.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tasc_ngram_entropy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(TableEntropy), C.c_void_p]
+        L.tasc_ngram_entropy_noalloc.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.tasc_model_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(WeightPtrs), C.POINTER(C.c_void_p)]
         L.tasc_session_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                           C.c_size_t, C.POINTER(C.c_void_p)]
@@ -205,6 +206,12 @@ def tasc_ngram_entropy(ng: Ngram, order: int, coverage_ppm: int = 800000, stream
     out = TableEntropy()
     _check(lib().tasc_ngram_entropy(ng.handle, order, coverage_ppm, C.byref(out), _stream(stream)))
     return out
+
+
+def tasc_ngram_entropy_noalloc(ng: Ngram, order: int, coverage_ppm: int, out_device, stream=None):
+    """out_device: cuda uint8 tensor of sizeof(TableEntropy) bytes, written on the stream (no synchronisation)."""
+    assert out_device.is_cuda and out_device.numel() * out_device.element_size() >= C.sizeof(TableEntropy)
+    _check(lib().tasc_ngram_entropy_noalloc(ng.handle, order, coverage_ppm, _ptr(out_device), _stream(stream)))
 
 
 def tasc_tok_enrich(tokens, doc_offsets, vocab, n_max, budget, stream=None):

@@ -136,33 +136,49 @@ __global__ void k_select_pick(int pass, SelectState* st, u64* hist_entries, u64*
 }
 }  // namespace
 
-extern "C" tasc_status tasc_ngram_entropy(const tasc_ngram* ng, int32_t order, int32_t coverage_ppm, tasc_table_entropy* out,
-                                          void* stream) {
-    TASC_REQUIRE(ng && out, "ngram_entropy: null argument");
-    TASC_REQUIRE(order >= 1 && order <= ng->view.n_max, "ngram_entropy: order %d outside [1, %d]", order, ng->view.n_max);
-    TASC_REQUIRE(coverage_ppm >= 0 && coverage_ppm <= 1000000, "ngram_entropy: coverage_ppm %d outside [0, 1000000]", coverage_ppm);
-    hipStream_t st = (hipStream_t)stream;
+// which table an order names: base address of the first count, stride between counts, number of slots
+struct TableSpan {
     const unsigned char* base;
     size_t stride;
     u64 n;
+};
+static TableSpan table_span(const tasc_ngram* ng, int order) {
+    TableSpan t;
     if (order == 1) {
-        base = reinterpret_cast<const unsigned char*>(ng->unigram);
-        stride = sizeof(u32);
-        n = (u64)ng->view.vocab;
+        t.base = reinterpret_cast<const unsigned char*>(ng->unigram);
+        t.stride = sizeof(u32);
+        t.n = (u64)ng->view.vocab;
     } else {
         const TascSlot* slots = ng->slots[order][1];
-        base = reinterpret_cast<const unsigned char*>(slots) + offsetof(TascSlot, a);
-        stride = sizeof(TascSlot);
-        n = slots ? ng->view.ord[order].full_mask + 1 : 0;
+        t.base = reinterpret_cast<const unsigned char*>(slots) + offsetof(TascSlot, a);
+        t.stride = sizeof(TascSlot);
+        t.n = slots ? ng->view.ord[order].full_mask + 1 : 0;
     }
-    if (!base) n = 0;
-    int blocks = (int)((n + kStatThreads - 1) / kStatThreads);
-    blocks = blocks < 1 ? 1 : (blocks > kStatBlocksMax ? kStatBlocksMax : blocks);
-    // scratch: partial sums, two 256-bin histograms, the select state and the result
-    const size_t part_bytes = (size_t)blocks * (2 * sizeof(u64) + 2 * sizeof(double));
-    const size_t bytes = part_bytes + 2 * 256 * sizeof(u64) + sizeof(SelectState) + sizeof(tasc_table_entropy);
-    unsigned char* scratch = nullptr;
-    TASC_HIP(hipMalloc(&scratch, bytes));
+    if (!t.base || (order != 1 && !ng->slots[order][1])) t.n = 0;
+    return t;
+}
+static int stat_blocks(u64 n) {
+    int blocks = (int)((n + kStatThreads - 1) / kStatThreads < (u64)kStatBlocksMax ? (n + kStatThreads - 1) / kStatThreads : (u64)kStatBlocksMax);
+    return blocks < 1 ? 1 : blocks;
+}
+// scratch of one call: partial sums, two 256-bin histograms, the select state and the result
+static size_t stat_scratch_bytes(int blocks) {
+    return (size_t)blocks * (2 * sizeof(u64) + 2 * sizeof(double)) + 2 * 256 * sizeof(u64) + sizeof(SelectState) + sizeof(tasc_table_entropy);
+}
+#define STAT_SCRATCH_MAX (kStatBlocksMax * 32 + 2 * 256 * 8 + 64 + 64)
+
+__global__ void k_stat_clear(u64* p, int n_words) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+__global__ void k_stat_result(const tasc_table_entropy* res, tasc_table_entropy* out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *out = *res;
+}
+
+// Enqueues the whole computation on `st`; *res_out = where the result will be (inside `scratch`).  `scratch` must hold
+// stat_scratch_bytes(blocks) zero bytes when the first kernel runs: cleared here by a fill kernel (a memset node in a
+// captured graph is not safe to replay, a kernel is).
+static tasc_status enqueue_entropy(const TableSpan& t, int blocks, int coverage_ppm, unsigned char* scratch, hipStream_t st,
+                                   tasc_table_entropy** res_out) {
     u64* part_n = reinterpret_cast<u64*>(scratch);
     u64* part_t = part_n + blocks;
     double* part_l = reinterpret_cast<double*>(part_t + blocks);
@@ -171,31 +187,87 @@ extern "C" tasc_status tasc_ngram_entropy(const tasc_ngram* ng, int32_t order, i
     u64* hist_m = hist_e + 256;
     SelectState* state = reinterpret_cast<SelectState*>(hist_m + 256);
     tasc_table_entropy* res = reinterpret_cast<tasc_table_entropy*>(state + 1);
-    tasc_status rc = TASC_OK;
-    auto fail = [&](hipError_t e, const char* what) {
-        tasc_set_error("ngram_entropy: %s -> %s", what, hipGetErrorString(e));
-        rc = TASC_EHIP;
-    };
-    hipError_t e = hipMemsetAsync(scratch, 0, bytes, st);
-    if (e != hipSuccess) fail(e, "clear");
-    if (rc == TASC_OK) {
-        k_table_moments<<<dim3(blocks), dim3(kStatThreads), 0, st>>>(base, stride, n, part_n, part_t, part_l, part_q);
-        k_table_finish<<<dim3(1), dim3(64), 0, st>>>(part_n, part_t, part_l, part_q, blocks, coverage_ppm, res, state);
-        for (int pass = 3; pass >= 0; --pass) {
-            k_select_hist<<<dim3(blocks), dim3(kStatThreads), 0, st>>>(base, stride, n, pass, state, hist_e, hist_m);
-            k_select_pick<<<dim3(1), dim3(256), 0, st>>>(pass, state, hist_e, hist_m, res);
-        }
-        e = hipGetLastError();
-        if (e != hipSuccess) fail(e, "launch");
+    const int words = (int)(stat_scratch_bytes(blocks) / 8);
+    k_stat_clear<<<dim3((words + 255) / 256), dim3(256), 0, st>>>(reinterpret_cast<u64*>(scratch), words);
+    k_table_moments<<<dim3(blocks), dim3(kStatThreads), 0, st>>>(t.base, t.stride, t.n, part_n, part_t, part_l, part_q);
+    k_table_finish<<<dim3(1), dim3(64), 0, st>>>(part_n, part_t, part_l, part_q, blocks, coverage_ppm, res, state);
+    for (int pass = 3; pass >= 0; --pass) {
+        k_select_hist<<<dim3(blocks), dim3(kStatThreads), 0, st>>>(t.base, t.stride, t.n, pass, state, hist_e, hist_m);
+        k_select_pick<<<dim3(1), dim3(256), 0, st>>>(pass, state, hist_e, hist_m, res);
     }
+    TASC_LAUNCH_CHECK();
+    *res_out = res;
+    return TASC_OK;
+}
+
+extern "C" tasc_status tasc_ngram_entropy(const tasc_ngram* ng, int32_t order, int32_t coverage_ppm, tasc_table_entropy* out,
+                                          void* stream) {
+    TASC_REQUIRE(ng && out, "ngram_entropy: null argument");
+    TASC_REQUIRE(order >= 1 && order <= ng->view.n_max, "ngram_entropy: order %d outside [1, %d]", order, ng->view.n_max);
+    TASC_REQUIRE(coverage_ppm >= 0 && coverage_ppm <= 1000000, "ngram_entropy: coverage_ppm %d outside [0, 1000000]", coverage_ppm);
+    hipStream_t st = (hipStream_t)stream;
+    const TableSpan t = table_span(ng, order);
+    const int blocks = stat_blocks(t.n);
+    unsigned char* scratch = nullptr;
+    TASC_HIP(hipMalloc(&scratch, stat_scratch_bytes(blocks)));
+    tasc_table_entropy* res = nullptr;
+    tasc_status rc = enqueue_entropy(t, blocks, coverage_ppm, scratch, st, &res);
     tasc_table_entropy host;
     if (rc == TASC_OK) {
-        e = hipMemcpyAsync(&host, res, sizeof(host), hipMemcpyDeviceToHost, st);
+        hipError_t e = hipMemcpyAsync(&host, res, sizeof(host), hipMemcpyDeviceToHost, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
-        if (e != hipSuccess) fail(e, "read back");
+        if (e != hipSuccess) {
+            tasc_set_error("ngram_entropy: read back -> %s", hipGetErrorString(e));
+            rc = TASC_EHIP;
+        }
     }
     hipError_t ef = hipFree(scratch);
-    if (rc == TASC_OK && ef != hipSuccess) fail(ef, "free");
+    if (rc == TASC_OK && ef != hipSuccess) {
+        tasc_set_error("ngram_entropy: free -> %s", hipGetErrorString(ef));
+        rc = TASC_EHIP;
+    }
     if (rc == TASC_OK) *out = host;
     return rc;
+}
+
+// ---------------------------------------------------------------- the same, allocating nothing
+// The scratch of tasc_ngram_entropy in a fixed array that every call on a device shares (each device holds its own copy
+// of the array at its own address: the address is looked up once per device and kept).
+static __device__ __align__(256) unsigned char scratch[STAT_SCRATCH_MAX];
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices];
+
+extern "C" tasc_status tasc_ngram_entropy_noalloc(const tasc_ngram* ng, int32_t order, int32_t coverage_ppm,
+                                                  tasc_table_entropy* out_device, void* stream) {
+    TASC_REQUIRE(ng && out_device, "ngram_entropy_noalloc: null argument");
+    TASC_REQUIRE(order >= 1 && order <= ng->view.n_max, "ngram_entropy_noalloc: order %d outside [1, %d]", order, ng->view.n_max);
+    TASC_REQUIRE(coverage_ppm >= 0 && coverage_ppm <= 1000000, "ngram_entropy_noalloc: coverage_ppm %d outside [0, 1000000]",
+                 coverage_ppm);
+    hipStream_t st = (hipStream_t)stream;
+    const TableSpan t = table_span(ng, order);
+    if (t.n > (u64)TASC_ENTROPY_NOALLOC_MAX_SLOTS) {
+        tasc_set_error("ngram_entropy_noalloc: the table of order %d has %llu slots, the fixed scratch serves at most %llu", order,
+                       (unsigned long long)t.n, (unsigned long long)TASC_ENTROPY_NOALLOC_MAX_SLOTS);
+        return TASC_ENOMEM;
+    }
+    const int blocks = stat_blocks(t.n);
+    if (stat_scratch_bytes(blocks) > (size_t)STAT_SCRATCH_MAX) {
+        tasc_set_error("ngram_entropy_noalloc: %zu bytes of scratch needed, %d available", stat_scratch_bytes(blocks), STAT_SCRATCH_MAX);
+        return TASC_ENOMEM;
+    }
+    int dev = 0;
+    TASC_HIP(hipGetDevice(&dev));
+    TASC_REQUIRE(dev >= 0 && dev < kMaxDevices, "ngram_entropy_noalloc: device %d outside [0, %d)", dev, kMaxDevices);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* p = nullptr;
+        TASC_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        TASC_REQUIRE(p != nullptr, "ngram_entropy_noalloc: the scratch array has no device address");
+        g_scratch_ptr[dev] = p;
+    }
+    tasc_table_entropy* res = nullptr;
+    tasc_status rc = enqueue_entropy(t, blocks, coverage_ppm, g_scratch_ptr[dev], st, &res);
+    if (rc != TASC_OK) return rc;
+    k_stat_result<<<dim3(1), dim3(64), 0, st>>>(res, out_device);
+    TASC_LAUNCH_CHECK();
+    return TASC_OK;
 }
