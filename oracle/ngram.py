@@ -132,6 +132,51 @@ def build_tables_flat(tokens, doc_off, vocab, n_max, p_min):
     return NgramTables(n_max, p_min, orders, unigram, int(np.argmax(unigram)))
 
 
+class _LazyOrder:
+    """M_n of a large corpus, one context at a time: get(ctx) counts the successors of ctx when it is first asked
+    for, by the definition ([M]: the n-gram frequencies of the corpus, pruned at p_min), over the positions where the
+    context's first token occurs."""
+
+    def __init__(self, owner, n):
+        self.owner, self.n, self.seen = owner, n, {}
+
+    def get(self, ctx, default=None):
+        ctx = tuple(int(t) for t in ctx)
+        if ctx not in self.seen:
+            self.seen[ctx] = self.owner.successors(ctx)
+        return self.seen[ctx] or default
+
+
+class LazyTables:
+    """The same object as build_tables_flat returns, for corpora whose full tables are too large to build in a test:
+    the tables of every order answer single-context queries on demand.  Only `orders[n].get(ctx)`, `unigram`,
+    `fallback`, `n_max` and `p_min` exist (what backoff / propose / draft use)."""
+
+    def __init__(self, tokens, doc_off, vocab, n_max, p_min):
+        self.tokens = np.asarray(tokens)
+        self.doc_off = np.asarray(doc_off, dtype=np.int64)
+        self.n_max, self.p_min = n_max, p_min
+        self.by_token = np.argsort(self.tokens, kind="stable").astype(np.int32)          # positions grouped by token
+        self.unigram = np.bincount(self.tokens, minlength=vocab).astype(np.int64)
+        self.first = np.concatenate([[0], np.cumsum(self.unigram)])                     # group of token t: [first[t], first[t+1])
+        self.fallback = int(np.argmax(self.unigram))
+        self.orders = {n: _LazyOrder(self, n) for n in range(2, n_max + 1)}
+
+    def successors(self, ctx):
+        """{x: count} over the windows ctx + (x,) that lie inside one output, counts below p_min dropped."""
+        n = len(ctx) + 1
+        t0 = ctx[0]
+        if t0 < 0 or t0 + 1 >= self.first.shape[0]:
+            return {}
+        pos = self.by_token[self.first[t0]:self.first[t0 + 1]].astype(np.int64)
+        doc_end = self.doc_off[np.searchsorted(self.doc_off, pos, side="right")]        # end of the output holding pos
+        pos = pos[pos + n <= doc_end]
+        for j in range(1, n - 1):
+            pos = pos[self.tokens[pos + j] == ctx[j]]
+        succ = Counter(self.tokens[pos + n - 1].tolist())
+        return {int(x): int(c) for x, c in succ.items() if c >= self.p_min}
+
+
 def split_docs(tokens, doc_off):
     return [tokens[doc_off[i]:doc_off[i + 1]] for i in range(len(doc_off) - 1)]
 

@@ -128,3 +128,48 @@ def test_drafts_match_oracle(lam, p_min_ctx):
             assert (committed[:len(prompts[b])] == prompts[b]).all() and len(committed) == len(prompts[b]) + 1
             want = ON.draft(ref, committed, k, lam, p_min_ctx)
             assert got[b].tolist() == want, f"sequence {b}, k {k}: {got[b].tolist()} vs oracle {want}"
+
+
+@pytest.mark.parametrize("lam", [65536, 49152, 16384, 0])
+def test_drafts_wide_keys_match_oracle(lam):
+    """Vocabulary 151,936 and n_max 5: contexts of 4 tokens are 72-bit keys, full 5-grams 90 bits, so every probe of the
+    two highest orders goes through the high key word.  Corpus documents (with noise) as prompts, repeated text, a run
+    of one token; drafts bit-exact against the oracle at four mixture weights."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    cfg = W.get_config("cfg1").scaled(vocab=151936, n_max=5, n_docs=3000, batch=12, gen_len=8, prompt_len=96)
+    rig = Rig(cfg, max_rows=16)
+    tok, off = rig.corpus
+    assert int(tok.max()) >= 1 << 17                       # tokens that need all 18 bits
+    ref = ON.build_tables_flat(tok, off, cfg.vocab, cfg.n_max, cfg.p_min)
+    assert len(ref.orders[5]) > 100 and len(ref.orders[4]) > 100
+    rng = np.random.default_rng(lam + 17)
+    prompts = []
+    for b in range(cfg.batch):
+        d = rng.integers(0, cfg.n_docs)
+        p = tok[off[d]:off[d + 1]].copy()[:rng.integers(6, 90)]
+        if b % 3 == 0:
+            p = np.concatenate([p, p])[:96]                # repeated text: the context source matches at order 5
+        if b == 5:
+            p = np.full(50, 151935, dtype=np.int32)        # a run of the largest token id
+        if b == 7:
+            p = np.concatenate([p[:20], np.array([131072, 151935, 131073, 262143 % 151936], dtype=np.int32), p[:20]])
+        prompts.append(p.astype(np.int32))
+    flat = np.concatenate(prompts)
+    poff = np.cumsum([0] + [len(p) for p in prompts]).astype(np.int64)
+    T.tasc_session_prefill(rig.model, rig.session, flat, poff, cfg.gen_len)
+    matched_high = 0
+    for k in (1, 5, 8):
+        params = T.spec_params(k, lam, 1, 1)
+        drafts = torch.zeros((cfg.batch, k), dtype=torch.int32, device="cuda")
+        T.tasc_draft(rig.ng, rig.session, params, drafts)
+        got = drafts.cpu().numpy()
+        for b in range(cfg.batch):
+            committed = T.tasc_session_get_tokens(rig.session, b)
+            want = ON.draft(ref, committed, k, lam, 1)
+            assert got[b].tolist() == want, f"lambda {lam} sequence {b}, k {k}: {got[b].tolist()} vs oracle {want}"
+            m = ON.backoff(ref, [int(t) for t in committed])
+            matched_high += m is not None and m[0] >= 4
+    if lam > 0:
+        assert matched_high > 0, "no sequence reached a corpus context of 3+ tokens: the wide keys went untested"

@@ -206,3 +206,28 @@ def test_draft_worked_example():
     # drafts extend the running context but not the statistics: after 7 the context knows 7 -> 0
     assert got[1] == 0
     assert len(O.draft(corp, [6, 6, 6], 5, 49152)) == 5
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_lazy_tables_equal_the_full_tables(seed):
+    """LazyTables (single-context counting for corpora too large for full tables) against the definition: every
+    context of every order, contexts that do not occur, and whole drafts."""
+    rng = random.Random(900 + seed)
+    vocab = rng.choice([3, 6, 40])
+    docs = [[rng.randrange(vocab) for _ in range(rng.randint(0, 25))] for _ in range(rng.choice([1, 5, 30]))]
+    docs.append([1, 1, 1, 1, 2])
+    n_max, p_min = rng.choice([2, 4, 5]), rng.choice([1, 2, 3])
+    tokens = np.array([t for d in docs for t in d], dtype=np.int32)
+    off = np.cumsum([0] + [len(d) for d in docs]).astype(np.int64)
+    full = O.build_tables(docs, vocab, n_max, p_min)
+    lazy = O.LazyTables(tokens, off, vocab, n_max, p_min)
+    assert lazy.fallback == full.fallback and (lazy.unigram == full.unigram).all()
+    for n in range(2, n_max + 1):
+        unpruned = O.count_windows(docs, n)
+        contexts = {w[:n - 1] for w in unpruned} | {tuple(rng.randrange(vocab) for _ in range(n - 1)) for _ in range(30)}
+        for ctx in contexts:
+            assert (lazy.orders[n].get(ctx) or None) == (full.orders[n].get(ctx) or None), (n, ctx)
+    for _ in range(20):
+        seq = [rng.randrange(vocab) for _ in range(rng.randint(1, 30))]
+        lam = rng.choice([0, 16384, 49152, 65536])
+        assert O.draft(lazy, seq, 5, lam, 1) == O.draft(full, seq, 5, lam, 1)
