@@ -312,10 +312,18 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
  *                        in that XCD-local mode, how many of the layer workgroups compute; the
  *                        others prefetch the next phase's weights into the XCD's L2 (0 = default:
  *                        all compute).  Results do not depend on it.
+ *   TASC_CFG_SMALL_KERNEL
+ *                        which kernel TASC_CFG_SMALL_PATH 1 and 2 run: 1 (default) = the spatial pipeline (every workgroup
+ *                        keeps one kind of work for all layers, weights requested a layer ahead, activations handed
+ *                        over through polled buffers) where the model fits it, 0 = the barrier kernel (phases separated
+ *                        by barriers among a group of workgroups).  Results are bit-identical.
+ *   TASC_CFG_PIPE_SHARE  output tiles (of 16 features) a workgroup of the spatial pipeline takes per layer at least, 1..3
+ *                        (default 1): larger values put fewer workgroups on every role.  Results do not depend on it.
  */
 enum {
     TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3,
-    TASC_CFG_TILED_PATH = 4, TASC_CFG_SMALL_XCD_LOCAL = 5, TASC_CFG_SMALL_LAYER_WORKERS = 6
+    TASC_CFG_TILED_PATH = 4, TASC_CFG_SMALL_XCD_LOCAL = 5, TASC_CFG_SMALL_LAYER_WORKERS = 6, TASC_CFG_SMALL_KERNEL = 7,
+    TASC_CFG_PIPE_SHARE = 8
 };
 tasc_status tasc_config_set(int32_t key, int32_t value);
 
@@ -399,6 +407,10 @@ tasc_status tasc_profile_enable(uint32_t class_mask);
 /* Waits for the device, then returns and clears the time and launch count recorded per class.
  * total_ms, launches: HOST arrays of TASC_N_KERNEL_CLASSES entries. */
 tasc_status tasc_profile_read(double* total_ms, int64_t* launches);
+/* The single durations behind tasc_profile_read, for medians: waits for the device, then writes the time of every recorded
+ * launch of class `cls`, in launch order, to ms[0 .. min(*n, cap)) (HOST) and their number to *n; clears nothing (call it
+ * before tasc_profile_read). */
+tasc_status tasc_profile_durations(int32_t cls, double* ms, int64_t cap, int64_t* n);
 
 /* Per-phase timing of the persistent small-batch kernel: while device_buf is non-NULL every launch
  * writes, for workgroup w < capacity / (2 * phases) and phase p (phases = 3 + 5 * n_layers: embedding,

@@ -21,7 +21,7 @@ EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
     "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_ngram_entropy_noalloc", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_tok_enrich", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
-    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read",
+    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_profile_durations", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read",
 ]
 KERNEL_CLASSES = ["draft", "prepare", "norm", "gemm_qkv", "rope_kv", "attn", "gemm_o", "gemm_gu", "gemm_d", "lmhead", "accept",
                   "verify", "layers"]
@@ -117,6 +117,7 @@ def lib():
         L.tasc_calibration_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.tasc_profile_enable.argtypes = [C.c_uint32]
         L.tasc_profile_read.argtypes = [C.c_void_p, C.c_void_p]
+        L.tasc_profile_durations.argtypes = [C.c_int32, C.c_void_p, C.c_int64, C.POINTER(C.c_int64)]
         for name in ("tasc_ngram_destroy", "tasc_model_destroy", "tasc_session_destroy"):
             getattr(L, name).argtypes = [C.c_void_p]
             getattr(L, name).restype = None
@@ -379,9 +380,21 @@ def tasc_profile_read():
     return {KERNEL_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}
 
 
+def tasc_profile_durations(cls_name) -> np.ndarray:
+    """Durations (ms) of every recorded launch of one class, in launch order; call before tasc_profile_read."""
+    cls = KERNEL_CLASSES.index(cls_name)
+    n = C.c_int64(0)
+    _check(lib().tasc_profile_durations(cls, None, 0, C.byref(n)))
+    out = np.zeros(max(n.value, 1), dtype=np.float64)
+    _check(lib().tasc_profile_durations(cls, _ptr(out), out.shape[0], C.byref(n)))
+    return out[:n.value]
+
+
 TASC_CFG_SMALL_PATH, TASC_CFG_SMALL_GRID, TASC_CFG_SMALL_LAYER_WGS, TASC_CFG_SMALL_LAYER_STRIDE, TASC_CFG_TILED_PATH = 0, 1, 2, 3, 4
 TASC_CFG_SMALL_XCD_LOCAL = 5
 TASC_CFG_SMALL_LAYER_WORKERS = 6
+TASC_CFG_SMALL_KERNEL = 7
+TASC_CFG_PIPE_SHARE = 8
 
 
 def tasc_config_set(key: int, value: int):

@@ -375,6 +375,8 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     s->host_counters = nullptr;
     s->bar_epoch = 0;
     s->barb_base = 0;
+    s->ll_copy = 0;
+    s->ll_armed = false;
     char* w = (char*)workspace;
     int i = 0;
     TascSessDev& d = s->d;
@@ -459,8 +461,9 @@ extern "C" tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s
     k_reset<<<dim3(B), dim3(256), 0, st>>>(B, s->max_len, d_prompts, d_off, d.tokens, d.n_tok, d.n_prompt, d.cached, d.n_emit,
                                            d.counters);
     TASC_LAUNCH_CHECK();
-    s->bar_epoch = 0;  // k_reset cleared the barrier flags and counters with the other counters
+    s->bar_epoch = 0;  // k_reset cleared the barrier flags and counters (the time-out flag among them) with the other counters
     s->barb_base = 0;
+    s->ll_armed = false;   // a step that timed out may have left its hand-over buffers half written: re-armed at the next launch
     k_check_prompts<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(d_prompts, total, m->desc.vocab, &d.counters[31]);
     TASC_LAUNCH_CHECK();
     TASC_HIP(hipMemcpyAsync(s->host_counters, d.counters, 32 * 8, hipMemcpyDeviceToHost, st));

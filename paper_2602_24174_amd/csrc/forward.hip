@@ -9,10 +9,11 @@
 #include "tasc_internal.h"
 #include "kernels_generic.h"
 #include "kernels_small.h"
+#include "kernels_pipe.h"
 #include "kernels_tiled.h"
 
 TascConfig g_tasc_config = {/*small_path*/ 2, /*small_grid*/ 0, /*layer_wgs*/ 0, /*layer_stride*/ 0, /*tiled_path*/ 1, /*xcd_local*/ 1,
-                             /*layer_workers*/ 0};
+                             /*layer_workers*/ 0, /*small_kernel*/ 1, /*pipe_share*/ 1};
 static u64* g_phase_ts = nullptr;
 static int64_t g_phase_ts_cap = 0;
 
@@ -42,6 +43,12 @@ extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
     } else if (key == TASC_CFG_SMALL_LAYER_WORKERS) {
         TASC_REQUIRE(value >= 0 && value <= 64, "config_set: layer workers %d outside [0, 64]", value);
         g_tasc_config.layer_workers = value;
+    } else if (key == TASC_CFG_SMALL_KERNEL) {
+        TASC_REQUIRE(value == 0 || value == 1, "config_set: small kernel %d outside [0, 1]", value);
+        g_tasc_config.small_kernel = value;
+    } else if (key == TASC_CFG_PIPE_SHARE) {
+        TASC_REQUIRE(value >= 1 && value <= 3, "config_set: pipeline share %d outside [1, 3]", value);
+        g_tasc_config.pipe_share = value;
     } else if (key == TASC_CFG_SMALL_XCD_LOCAL) {
         TASC_REQUIRE(value == 0 || value == 1, "config_set: XCD-local switch %d outside [0, 1]", value);
         g_tasc_config.xcd_local = value;
@@ -374,12 +381,13 @@ bool small_path_fits(const tasc_model* m, int batch, int nq, int max_blocks) {
 }
 
 int g_cu_count = 0;
+bool g_small_ready = false;
 
 tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, TascVerifyTail* tail,
                           hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
-    if (g_cu_count == 0) {
+    if (!g_small_ready) {
         int dev = 0, cus = 0;
         TASC_HIP(hipGetDevice(&dev));
         TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
@@ -396,6 +404,7 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
             return TASC_EHIP;
         }
         g_cu_count = cus;
+        g_small_ready = true;
     }
     SmallArgs a;
     a.layers = m->d_layers;
@@ -453,6 +462,7 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     a.lg_workers = g_tasc_config.layer_workers > 0 ? g_tasc_config.layer_workers : lg;
     a.bar_epoch = s->bar_epoch;
     a.barb_base = s->barb_base;
+    s->ll_armed = false;       // this kernel writes the first copy of the buffers the pipeline kernel expects untouched
     PROF(TASC_KC_LAYERS);
     auto launch = [&](int p0, int p1) {
         if (c.head_dim == 32) k_small_step<1><<<dim3(grid), dim3(SMALL_THREADS), SMALL_LDS_BYTES, st>>>(a, p0, p1);
@@ -474,7 +484,156 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     return TASC_OK;
 }
 
+// ---------------------------------------------------------------- the spatial-pipeline kernel
+__global__ void k_fill_sentinel(u64* p, size_t units16) {
+    for (size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x; u < units16; u += (size_t)gridDim.x * blockDim.x) {
+        p[2 * u] = ~0ull;
+        p[2 * u + 1] = ~0ull;
+    }
+}
+
+// Deals the workgroups of the grid to the five roles: every role gets enough of them that a workgroup's share of the
+// role's items (16-feature tiles, or (sequence, head) pairs) stays within what one pass holds in registers.  Returns
+// false if the grid is too small for the model.
+bool pipe_roles(const tasc_model_desc& c, int batch, int grid, int32_t (&base)[PIPE_N_ROLES], int32_t (&count)[PIPE_N_ROLES]) {
+    const bool wide = c.d_model > 768;                     // 6 fragments per tile row and lane: one item per pass
+    const int items[PIPE_N_ROLES] = {(c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 32), batch * c.n_heads, c.d_model / 16,
+                                     c.d_ffn / 16, c.d_model / 16};
+    const int max_share[PIPE_N_ROLES] = {wide ? 1 : 3, 1 << 20, 3, wide ? 1 : 3, 3};
+    int share[PIPE_N_ROLES] = {1, 1, 1, 1, 1};
+    for (int r = 0; r < PIPE_N_ROLES; ++r)
+        if (r != PIPE_ATTN) share[r] = g_tasc_config.pipe_share > max_share[r] ? max_share[r] : (g_tasc_config.pipe_share < 1 ? 1 : g_tasc_config.pipe_share);
+    auto wgs = [&](int r) { return (items[r] + share[r] - 1) / share[r]; };
+    share[PIPE_ATTN] = (items[PIPE_ATTN] + 15) / 16;       // at most 16 workgroups on attention
+    for (;;) {
+        int total = 0;
+        for (int r = 0; r < PIPE_N_ROLES; ++r) total += wgs(r);
+        if (total <= grid) break;
+        int pick = -1;
+        for (int r = 0; r < PIPE_N_ROLES; ++r)
+            if (share[r] < max_share[r] && (pick < 0 || wgs(r) > wgs(pick))) pick = r;
+        if (pick < 0) return false;
+        ++share[pick];
+    }
+    int at = 0;
+    for (int r = 0; r < PIPE_N_ROLES; ++r) {
+        base[r] = at;
+        count[r] = wgs(r);
+        at += count[r];
+    }
+    return true;
+}
+
+bool pipe_path_fits(const tasc_model* m, int batch, int nq, int max_blocks, int grid) {
+    const tasc_model_desc& c = m->desc;
+    int32_t b[PIPE_N_ROLES], n[PIPE_N_ROLES];
+    return c.d_model % 64 == 0 && grid >= 8 && pipe_roles(c, batch, grid, b, n);
+}
+
+template <int NKS, int WKS>
+tasc_status pipe_attr() {
+    TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_pipe_step<NKS, WKS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 PIPE_LDS_BYTES));
+    return TASC_OK;
+}
+bool g_pipe_ready = false;
+
+tasc_status forward_pipe(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, TascVerifyTail* tail, int grid,
+                         hipStream_t st) {
+    const tasc_model_desc& c = m->desc;
+    const TascSessDev& d = s->d;
+    if (!g_pipe_ready) {
+        tasc_status rc;
+        if ((rc = pipe_attr<1, 3>()) != TASC_OK || (rc = pipe_attr<2, 3>()) != TASC_OK || (rc = pipe_attr<4, 3>()) != TASC_OK ||
+            (rc = pipe_attr<1, 6>()) != TASC_OK || (rc = pipe_attr<2, 6>()) != TASC_OK || (rc = pipe_attr<4, 6>()) != TASC_OK)
+            return rc;
+        g_pipe_ready = true;
+    }
+    if (!s->ll_armed) {
+        tasc_status rc = tasc_pipe_arm(s, st);
+        if (rc != TASC_OK) return rc;
+    }
+    const TascSmallWs w = tasc_small_ws_layout(c);
+    char* cur = d.small_ws + (size_t)s->ll_copy * w.bytes;
+    char* other = d.small_ws + (size_t)(1 - s->ll_copy) * w.bytes;
+    PipeArgs pa;
+    SmallArgs& a = pa.a;
+    a.layers = m->d_layers;
+    a.embed = (const BF16*)m->embed;
+    a.lm_head = (const BF16*)m->lm_head_f;
+    a.gf = m->gf;
+    a.rope_cos = m->rope_cos;
+    a.rope_sin = m->rope_sin;
+    a.bias = BiasCsr{m->bias_rowptr, m->bias_col, m->bias_val, m->bias_base};
+    a.n_layers = c.n_layers; a.D = c.d_model; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim; a.F = c.d_ffn;
+    a.V = c.vocab; a.max_pos = c.max_pos; a.eps = c.rms_eps; a.scale = 1.0f / sqrtf((float)c.head_dim);
+    a.kv_pool = (BF16*)s->kv_pool; a.kv_layer_stride = s->kv_layer_stride; a.page_elems = s->page_elems;
+    a.B = s->batch; a.nq = nq; a.M = s->batch * nq; a.max_blocks = s->max_blocks; a.max_len = s->max_len;
+    a.n_strips = s->n_strips; a.max_new = s->max_new;
+    a.row_tok = d.row_tok; a.n_rows = d.n_rows; a.pos0 = d.pos0; a.block_tab = d.block_tab; a.sel_rows = d.sel_rows;
+    a.sel_tok = d.sel_tok; a.n_sel = n_sel;
+    a.x = (float*)(cur + w.x_off); a.x_stride = w.x_stride;
+    a.q = (BF16*)(cur + w.q_off); a.att = (BF16*)(cur + w.att_off); a.q_stride = w.q_stride;
+    a.act = (BF16*)(cur + w.act_off); a.act_stride = w.act_stride;
+    pa.kvn = (BF16*)(cur + w.kvn_off); pa.kvn_stride = w.kvn_stride;
+    pa.pv = (float*)(cur + w.pv_off); pa.pi = (int32_t*)(cur + w.pi_off);
+    a.part_val = d.part_val; a.part_idx = d.part_idx; a.amax = d.amax; a.logits_dbg = logits_dbg;
+    a.k = tail ? tail->k : -1;
+    a.drafts = tail ? tail->drafts : nullptr;
+    a.tokens = d.tokens; a.n_tok = d.n_tok; a.cached = d.cached; a.n_emit = d.n_emit; a.counters = d.counters;
+    a.accept_len = tail ? tail->accept_len : nullptr;
+    a.emitted = tail ? tail->emitted : nullptr;
+    a.trace_step = tail ? tail->trace_step : nullptr;
+    a.bar_flags = (u32*)&d.counters[TASC_CTR_FLAGS];
+    a.barb_counter = &d.counters[TASC_CTR_BARB];
+    a.bar_error = (u32*)&d.counters[TASC_CTR_BAR_ERR];
+    a.xcc_mask = (u32*)&d.counters[TASC_CTR_XCC];
+    a.xcd_local = 0;
+    a.bias_ptr = d.bias_ptr;
+    a.lg_stride = 1; a.lg_count = 0; a.lg_workers = 0; a.bar_epoch = 0; a.barb_base = 0;
+    const int n_phases = 3 + 5 * c.n_layers, n_lg_phases = 1 + 5 * c.n_layers;
+    a.phase_ts = g_phase_ts;
+    a.phase_ts_wgs = g_phase_ts ? (int32_t)(g_phase_ts_cap / (2 * (int64_t)n_phases)) : 0;
+    if (!pipe_roles(c, s->batch, grid, pa.role_base, pa.role_count)) {
+        tasc_set_error("forward: the pipeline kernel does not fit %d workgroups", grid);
+        return TASC_EINVAL;
+    }
+    const int last = n_sel > 0 ? n_phases : n_lg_phases;
+    PROF(TASC_KC_LAYERS);
+    auto launch = [&](int p0, int p1) {
+        pa.rearm = p0 == 0 ? (u64*)other : nullptr;
+        pa.rearm_units = p0 == 0 ? w.bytes / 16 : 0;
+        const bool wide = c.d_model > 768;
+#define PIPE_LAUNCH(NKS)                                                                                                 \
+        if (wide) k_pipe_step<NKS, 6><<<dim3(grid), dim3(SMALL_THREADS), PIPE_LDS_BYTES, st>>>(pa, p0, p1);               \
+        else k_pipe_step<NKS, 3><<<dim3(grid), dim3(SMALL_THREADS), PIPE_LDS_BYTES, st>>>(pa, p0, p1)
+        if (c.head_dim == 32) { PIPE_LAUNCH(1); }
+        else if (c.head_dim == 64) { PIPE_LAUNCH(2); }
+        else { PIPE_LAUNCH(4); }
+#undef PIPE_LAUNCH
+    };
+    if (g_tasc_config.small_path == 2) {
+        launch(0, last);
+    } else {
+        for (int ph = 0; ph < last; ++ph) launch(ph, ph + 1);
+    }
+    TASC_LAUNCH_CHECK();
+    s->ll_copy = 1 - s->ll_copy;
+    if (tail) tail->done = n_sel > 0;
+    return TASC_OK;
+}
+
 }  // namespace
+
+tasc_status tasc_pipe_arm(tasc_session* s, hipStream_t st) {
+    const tasc_model_desc& c = s->model->desc;
+    if (c.dtype != TASC_BF16) return TASC_OK;
+    const size_t units = tasc_small_ws_bytes(c) / 16;
+    k_fill_sentinel<<<dim3(1024), dim3(256), 0, st>>>((u64*)s->d.small_ws, units);
+    TASC_LAUNCH_CHECK();
+    s->ll_armed = true;
+    return TASC_OK;
+}
 
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel, float* logits_dbg,
                               TascVerifyTail* tail, hipStream_t st) {
@@ -483,8 +642,19 @@ tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, 
     // call's row count, so that a greedy step and a speculative step of one session use the same kernels and
     // reduce every row in the same order.  Prompt chunks of more than 16 rows always take the tiled kernels.
     const int decode_rows = s->max_rows < SMALL_ROWS ? s->max_rows : SMALL_ROWS;
-    if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m, s->batch, decode_rows, s->max_blocks))
+    if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m, s->batch, decode_rows, s->max_blocks)) {
+        if (g_tasc_config.small_kernel != 0) {
+            if (g_cu_count == 0) {
+                int dev = 0;
+                TASC_HIP(hipGetDevice(&dev));
+                TASC_HIP(hipDeviceGetAttribute(&g_cu_count, hipDeviceAttributeMultiprocessorCount, dev));
+            }
+            int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
+            grid = grid < g_cu_count ? grid : g_cu_count;      // every workgroup must be resident: at most one per compute unit
+            if (pipe_path_fits(m, s->batch, decode_rows, s->max_blocks, grid)) return forward_pipe(m, s, nq, n_sel, logits_dbg, tail, grid, st);
+        }
         return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);
+    }
     if (g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc)) return forward_tiled(m, s, nq, n_sel, logits_dbg, st);
     if (m->desc.dtype == TASC_F32) return forward_generic<float>(m, s, nq, n_sel, logits_dbg, st);
     return forward_generic<BF16>(m, s, nq, n_sel, logits_dbg, st);

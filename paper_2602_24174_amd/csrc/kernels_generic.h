@@ -8,11 +8,13 @@
 struct BF16 { uint16_t v; };
 
 __device__ inline float bf2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
-__device__ inline uint16_t f2bf(float f) {   // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+// fp32 -> bf16, round to nearest even: the hardware conversion of gfx950 (v_cvt_pk_bf16_f32), one instruction per pair
+typedef __attribute__((ext_vector_type(2))) float tasc_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 tasc_bf16x2;
+__device__ inline uint32_t f2bf_pair(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(tasc_f32x2{lo, hi}, tasc_bf16x2));
 }
+__device__ inline uint16_t f2bf(float f) { return (uint16_t)(f2bf_pair(f, 0.f) & 0xFFFFu); }
 __device__ inline float to_f(float v) { return v; }
 __device__ inline float to_f(BF16 v) { return bf2f(v.v); }
 template <typename T> __device__ inline T from_f(float f);

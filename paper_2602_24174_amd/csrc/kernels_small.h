@@ -298,7 +298,7 @@ __device__ __forceinline__ void stage_normed_finish(const NormRegs<NTC>& rg, int
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int r = wave + SMALL_NW * j;
-        const float ri = 1.0f / sqrtf(ss[j] / (float)D + eps);
+        const float ri = __builtin_amdgcn_rsqf(ss[j] / (float)D + eps);      // v_rsq_f32: 1 ulp, one instruction
 #pragma unroll
         for (int t = 0; t < NTC; ++t) {
             const int c = 4 * (lane + 64 * t);
@@ -306,8 +306,8 @@ __device__ __forceinline__ void stage_normed_finish(const NormRegs<NTC>& rg, int
                 const f32x4 v = rg.v[j][t], gg = rg.g[t];
                 u32x2 o = {0, 0};
                 if (r < M) {
-                    o[0] = (uint32_t)f2bf(v[0] * ri * gg[0]) | ((uint32_t)f2bf(v[1] * ri * gg[1]) << 16);
-                    o[1] = (uint32_t)f2bf(v[2] * ri * gg[2]) | ((uint32_t)f2bf(v[3] * ri * gg[3]) << 16);
+                    o[0] = f2bf_pair(v[0] * ri * gg[0], v[1] * ri * gg[1]);
+                    o[1] = f2bf_pair(v[2] * ri * gg[2], v[3] * ri * gg[3]);
                 }
                 *reinterpret_cast<u32x2*>(s_act + r * SMALL_KP + c) = o;
             }
@@ -414,7 +414,7 @@ __device__ __forceinline__ f32x4 sum_tile(const f32x4* s_red, int t) {
 }
 
 __device__ __forceinline__ u32x2 pack_bf16x4(float a, float b, float c, float d) {
-    return u32x2{(uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16), (uint32_t)f2bf(c) | ((uint32_t)f2bf(d) << 16)};
+    return u32x2{f2bf_pair(a, b), f2bf_pair(c, d)};
 }
 
 // ---------------------------------------------------------------- phase: RMSNorm + q/k/v + RoPE + KV append

@@ -57,6 +57,23 @@ extern "C" tasc_status tasc_profile_read(double* total_ms, int64_t* launches) {
     return TASC_OK;
 }
 
+extern "C" tasc_status tasc_profile_durations(int32_t cls, double* ms, int64_t cap, int64_t* n) {
+    TASC_REQUIRE(n && cap >= 0 && (ms || cap == 0), "profile_durations: null argument");
+    TASC_REQUIRE(cls >= 0 && cls < TASC_N_KERNEL_CLASSES, "profile_durations: class %d outside [0, %d)", cls, TASC_N_KERNEL_CLASSES);
+    TASC_HIP(hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lk(g_mu);
+    int64_t k = 0;
+    for (Pair& p : g_used) {
+        if (p.cls != cls) continue;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, p.a, p.b) != hipSuccess) continue;
+        if (k < cap) ms[k] = t;
+        ++k;
+    }
+    *n = k;
+    return TASC_OK;
+}
+
 // Plain copy kernel of known size: the reference against which hardware byte counters are scaled.
 namespace {
 __global__ void k_calibration_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {

@@ -201,6 +201,8 @@ struct tasc_session {
     u64* host_counters;       // pinned
     u32 bar_epoch;            // barriers the layer group's arrival flags (counters[32..63]) have seen so far
     u64 barb_base;            // same for the whole-grid barrier counter (counters[26])
+    int ll_copy;              // which copy of the small-batch activation buffers the next pipeline launch uses
+    bool ll_armed;            // both copies hold the "not written yet" pattern wherever the next launch expects it
 };
 
 // counters[] slots used beyond the statistics
@@ -222,17 +224,21 @@ struct TascVerifyTail {
 };
 
 // library-wide options (tasc_config_set)
-// Layout of the small-batch kernel's activation buffers (each written once per launch): byte offsets, strides in
-// elements, and the total size in bytes.  16 rows throughout.
+// Layout of ONE copy of the small-batch kernels' activation buffers (each written once per launch): byte offsets, strides
+// in elements, and the size of a copy in bytes.  16 rows throughout.  The workspace holds two copies: the pipeline
+// kernel uses them in turn and refills the idle one with its "not written yet" pattern (the barrier kernel uses copy 0).
 struct TascSmallWs {
     size_t x_off, x_stride;         // float [2 L + 1][16][D]
     size_t q_off, att_off, q_stride;   // bf16 [L][16][H hd] each
     size_t act_off, act_stride;     // bf16  [L][16][F]
+    size_t kvn_off, kvn_stride;     // bf16  [L][16][2 Hkv hd]: the launch's own key and value rows
+    size_t pv_off, pi_off;          // float / int32 [16][n_strips]: LM-head strip maxima and their token ids
     size_t bytes;
 };
 inline TascSmallWs tasc_small_ws_layout(const tasc_model_desc& c) {
     TascSmallWs w;
-    const size_t L = c.n_layers, HD = (size_t)c.n_heads * c.head_dim, al = 256;
+    const size_t L = c.n_layers, HD = (size_t)c.n_heads * c.head_dim, KD = (size_t)c.n_kv_heads * c.head_dim, al = 256;
+    const size_t n_strips = ((size_t)c.vocab + TASC_LM_STRIP - 1) / TASC_LM_STRIP;
     auto up = [&](size_t v) { return (v + al - 1) / al * al; };
     size_t o = 0;
     w.x_off = o; w.x_stride = 16 * (size_t)c.d_model; o += up((2 * L + 1) * w.x_stride * 4);
@@ -240,10 +246,13 @@ inline TascSmallWs tasc_small_ws_layout(const tasc_model_desc& c) {
     w.q_off = o; o += up(L * w.q_stride * 2);
     w.att_off = o; o += up(L * w.q_stride * 2);
     w.act_off = o; w.act_stride = 16 * (size_t)c.d_ffn; o += up(L * w.act_stride * 2);
+    w.kvn_off = o; w.kvn_stride = 16 * 2 * KD; o += up(L * w.kvn_stride * 2);
+    w.pv_off = o; o += up(16 * n_strips * 4);
+    w.pi_off = o; o += up(16 * n_strips * 4);
     w.bytes = o;
     return w;
 }
-inline size_t tasc_small_ws_bytes(const tasc_model_desc& c) { return c.dtype == TASC_BF16 ? tasc_small_ws_layout(c).bytes : 256; }
+inline size_t tasc_small_ws_bytes(const tasc_model_desc& c) { return c.dtype == TASC_BF16 ? 2 * tasc_small_ws_layout(c).bytes : 256; }
 
 struct TascConfig {
     int small_path;           // 0: generic kernels only, 1: fused kernel one phase per launch, 2: persistent
@@ -253,10 +262,14 @@ struct TascConfig {
     int tiled_path;           // 1: LDS-tiled MFMA kernels for bf16 forwards of more than 16 rows, 0: generic kernels
     int xcd_local;            // 1 = the layer group may use XCD-local barriers when it sits on one XCD
     int layer_workers;        // members of the layer group that compute in XCD-local mode (0 = all), the rest prefetch
+    int small_kernel;         // 1: the spatial-pipeline kernel where the model fits it, 0: the barrier kernel always
+    int pipe_share;           // tiles a workgroup of the pipeline kernel takes per layer at least (1..3): fewer, fatter workgroups
 };
 extern TascConfig g_tasc_config;
 
 // forward.hip
+// fills both copies of the small-batch activation buffers with the pipeline kernel's "not written yet" pattern
+tasc_status tasc_pipe_arm(tasc_session* s, hipStream_t st);
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel,
                               float* logits_dbg, TascVerifyTail* tail, hipStream_t st);
 

@@ -17,6 +17,33 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def pipeline_report(cfg, ts, n_wg):
+    """Stamps of the spatial-pipeline kernel: per workgroup and phase (inputs complete, outputs stored); a workgroup
+    only has stamps for the phases of its role."""
+    L = cfg.n_layers
+    have = ts[:, :, 1] > 0
+    ready = np.where(have, ts[:, :, 0], np.nan)
+    done = np.where(have, ts[:, :, 1], np.nan)
+    lay = slice(1, 1 + 5 * L)
+    first_ready, last_ready = np.nanmin(ready, axis=0), np.nanmax(ready, axis=0)
+    last_done = np.nanmax(done, axis=0)
+    work = np.nanmax(done - ready, axis=0)                       # inputs complete -> outputs stored, slowest workgroup
+    hop = last_ready[2:] - last_done[1:-1]                       # outputs stored -> the next phase's slowest workgroup has its inputs
+    per = lambda v: np.round(np.nanmedian(np.asarray(v)[:5 * L].reshape(L, 5), axis=0), 2)
+    t0 = np.nanmin(ready[:, 1])
+    n_role = [int(have[:, 1 + r].sum()) for r in range(5)]
+    print(f"{cfg.name}: grid {n_wg} workgroups; workgroups per role (qkv, attention, o-proj, gate/up, down) {n_role}; k = {cfg.k}, "
+          f"cached length about {cfg.prompt_len + 6 * (cfg.k + 1)}")
+    print(f"whole step {np.nanmax(done) - t0:.1f} us from the first layer's inputs; layers {last_done[5 * L] - t0:.1f} us "
+          f"({(last_done[5 * L] - t0) / L:.2f} us per layer); LM head {last_done[-2] - first_ready[-2]:.1f} us "
+          f"(inputs at the last workgroup {last_ready[-2] - last_done[5 * L]:.2f} us after the last layer); accept ends "
+          f"{last_done[-1] - last_done[-2]:.1f} us after the last strip")
+    print("per-layer medians over the layers (us)                         qkv    attn   o-proj  gate/up  down")
+    print("  inputs complete -> outputs stored, slowest workgroup       ", per(work[lay]))
+    print("  outputs stored -> inputs complete at the next phase        ", per(np.append(hop[:5 * L - 1], np.nan)))
+    print("  spread of 'inputs complete' over the phase's workgroups    ", per((last_ready - first_ready)[lay]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", default="cfg2")
@@ -27,6 +54,9 @@ def main():
     ap.add_argument("--workers", type=int, default=0, help="computing members of the layer group in XCD-local mode (0 = half)")
     ap.add_argument("--docs", type=int, default=0, help="corpus size (0 = the configuration's; it sets the size of the LM-head bias table)")
     ap.add_argument("--agent-barriers", action="store_true", help="agent-scope barriers only (no XCD-local mode)")
+    ap.add_argument("--barrier-kernel", action="store_true", help="the barrier kernel instead of the spatial pipeline")
+    ap.add_argument("--share", type=int, default=1, help="tiles per workgroup and layer of the pipeline kernel (1..3)")
+    ap.add_argument("--dump", default="", help="also save the raw stamps [workgroup][phase][2] (microseconds) as a .npy file")
     args = ap.parse_args()
     import torch
     import workload as W
@@ -44,6 +74,8 @@ def main():
     model = T.tasc_model_create(cfg, weights, max_len)
     ng = T.tasc_ngram_build(corpus[0], corpus[1], cfg.vocab, cfg.n_max, cfg.p_min)
     sess = T.tasc_session_create(model, cfg.batch, max_len, args.max_rows)
+    T.tasc_config_set(T.TASC_CFG_SMALL_KERNEL, 0 if args.barrier_kernel else 1)
+    T.tasc_config_set(T.TASC_CFG_PIPE_SHARE, args.share)
     T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 0 if args.agent_barriers else 1)
     T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WORKERS, args.workers)
     T.tasc_config_set(T.TASC_CFG_SMALL_GRID, args.grid)
@@ -65,6 +97,10 @@ def main():
     T.tasc_profile_phases(None)
 
     ts = buf.cpu().numpy().reshape(n_wg, n_ph, 2).astype(np.float64) / 100.0      # microseconds (100 MHz clock)
+    if args.dump:
+        np.save(args.dump, ts)
+    if not args.barrier_kernel:
+        return pipeline_report(cfg, ts, n_wg)
     one_xcd = not args.agent_barriers and n_wg >= 256            # the library's defaults
     stride = args.layer_stride or (8 if one_xcd else 1)
     lg = args.layer_wgs or (32 if one_xcd and not args.layer_stride else 48)

@@ -115,30 +115,38 @@ def test_measurement_forward_equals_oracle_forward():
     assert np.abs(got - want).max() < 2e-6          # float32 products against float64 ones
 
 
-@pytest.mark.parametrize("name,rows", [("cfg3", 7), ("cfg4", 9), ("cfg5", 5)])
-def test_logit_error_of_bf16_inputs_alone(name, rows):
+CONTEXT = 48          # prompt length of the GPU parity tests of the two deep models (tests/test_gpu_full.py)
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_logit_error_of_bf16_inputs_alone(name):
+    """The rows of one verify step (k + 1 of them) after a 48-token context, as the GPU tests of these models score
+    them; the error is taken over those rows (it grows with the context: with 5 rows and no context the 3B-class
+    figures are rms 1.6e-2 / maximum 0.09, with the context 2.2e-2 / 0.12)."""
     cfg = W.get_config(name)
+    rows = cfg.k + 1
     rng = np.random.default_rng(11)
-    toks = rng.integers(0, cfg.vocab, rows).tolist()
+    toks = rng.integers(0, cfg.vocab, CONTEXT + rows).tolist()
     gen = _Weights(cfg, 5)
     embed = gen.matrix("embed", (cfg.vocab, cfg.d_model)).copy()
     lm_head = gen.matrix("lm_head", (cfg.vocab, cfg.d_model))
     exact, inputs, inputs_p = _forward(cfg, toks, gen.layer, embed, lm_head, [IDENT, _bf16, _bf16], [IDENT, IDENT, _bf16])
     out = {}
+    exact = exact[-rows:]
     for label, z in (("inputs", inputs), ("inputs + softmax weights", inputs_p)):
-        d = np.abs(z - exact)
+        d = np.abs(z[-rows:] - exact)
         out[label] = (float(d.max()), float(np.sqrt((d ** 2).mean())), float((d > 5e-2).mean()))
         print(f"{name} ({cfg.n_layers} layers, d {cfg.d_model}, {rows} rows x {cfg.vocab} logits), bf16 {label}: "
               f"max |delta| {out[label][0]:.4f}, rms {out[label][1]:.4f}, share beyond 5e-2 {out[label][2]:.2e}; "
               f"logit std {exact.std():.3f}", flush=True)
-    worst, rms, share = out["inputs"]
-    # The finding this test records.  0.5B-class model: the rounding stays well inside the 5e-2 logit tolerance.  1.5B-
-    # and 3B-class models: rounding the matrix-product inputs alone reaches or passes it (the draws are seeded, so the
-    # figures repeat), which is why the GPU parity tests of those two hold the path to bounds derived from here
-    # (tests/test_gpu_full.py: rms 2.5e-2, maximum 1.5e-1, share beyond 5e-2 at most 1e-2).
+    worst, rms, share = out["inputs + softmax weights"]
+    # The finding this test records (the draws are seeded, so the figures repeat).  0.5B-class model: the rounding stays
+    # well inside the 5e-2 logit tolerance.  1.5B- and 3B-class models: rounding the inputs alone passes it, which is why
+    # the GPU parity tests of those two hold the path to bounds derived from here, about 1.4 times these figures
+    # (tests/test_gpu_full.py: DEEP_BOUNDS).
     if name == "cfg3":
         assert worst < 4e-2 and rms < 8e-3
-    else:
-        assert 8e-3 < rms < 2.5e-2 and worst < 1.5e-1 and share < 1e-2
+    if name == "cfg4":
+        assert 5e-2 < worst < 1e-1 and 1e-2 < rms < 1.7e-2 and share < 1e-3
     if name == "cfg5":
-        assert worst > 5e-2
+        assert 5e-2 < worst < 1.6e-1 and 1.7e-2 < rms < 2.7e-2 and share < 3.5e-2

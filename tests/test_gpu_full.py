@@ -4,8 +4,8 @@ those keys), step replay of drafts (oracle counts taken on demand from the full 
 speculative == greedy on every sequence, and logits of one sequence for the first verify steps.
 
 Logit tolerance: 5e-2 absolute for cfg2 and cfg3.  For the 1.5B- and 3B-class models that bound is below what bf16
-matrix-product inputs cost by themselves (tests/test_bf16_input_rounding.py measures it on the CPU: maximum 0.05-0.07
-at 28 layers / width 1536, 0.07-0.09 at 36 layers / width 2048), so there the tests assert THIS BUILD'S OWN bounds, derived
+matrix-product inputs cost by themselves (tests/test_bf16_input_rounding.py measures it on the CPU: maximum 0.07 at
+28 layers / width 1536, 0.12 at 36 layers / width 2048), so there the tests assert THIS BUILD'S OWN bounds, derived
 from that measurement: rms, maximum, the share of logits beyond 5e-2, and that no argmax with a clear margin flips."""
 import numpy as np
 import pytest
@@ -103,13 +103,16 @@ def test_full_size_config(name, max_rows, n_steps, sample):
     assert worst <= 5e-2
 
 
-# This build's own logit bounds for the 1.5B- and 3B-class models (see the module docstring): the CPU measurement of
-# bf16 matrix-product inputs alone gives rms 1.0e-2 - 1.7e-2, maximum 0.05 - 0.09 and up to 4e-3 of the logits beyond
-# 5e-2; the GPU path adds bf16 softmax weights and fp32 accumulation, both below that.
-OWN_RMS, OWN_MAX, OWN_SHARE = 2.5e-2, 1.5e-1, 1e-2
+# This build's own logit bounds for the 1.5B- and 3B-class models (see the module docstring): (rms, maximum, share of the
+# logits beyond 5e-2).  The CPU measurement of bf16 matrix-product inputs and softmax weights alone, in this test's
+# setting (a verify step after a 48-token prompt), gives rms 1.4e-2 / maximum 0.070 / share 3e-4 at 28 layers and width
+# 1536, and rms 2.2e-2 / maximum 0.12 / share 2.5e-2 at 36 layers and width 2048; the bounds are about 1.4 times that.
+DEEP_BOUNDS = {"cfg4": (2e-2, 1e-1, 2e-3), "cfg5": (3e-2, 1.8e-1, 4e-2)}
 
 
-def _check_deep_model_logits(label, got, z):
+def _check_deep_model_logits(name, got, z):
+    label = name + " model"
+    own_rms, own_max, own_share = DEEP_BOUNDS[name]
     d = np.abs(got - z)
     worst, rms, share = float(d.max()), float(np.sqrt((d ** 2).mean())), float((d > 5e-2).mean())
     top2 = np.sort(z, axis=-1)[:, -2:]
@@ -117,7 +120,7 @@ def _check_deep_model_logits(label, got, z):
     flips = [(i, float(margin[i])) for i in range(z.shape[0]) if int(np.argmax(got[i])) != int(np.argmax(z[i]))]
     print(f"{label}: max |logit - oracle| = {worst:.3e}, rms {rms:.3e}, share beyond 5e-2 {share:.2e}, "
           f"smallest top-1 margin {margin.min():.2f}, argmax flips {flips}", flush=True)
-    assert rms <= OWN_RMS and worst <= OWN_MAX and share <= OWN_SHARE
+    assert rms <= own_rms and worst <= own_max and share <= own_share
     assert all(m <= 0.2 for _, m in flips), "an argmax with a clear margin differs from the oracle's"
 
 
@@ -159,7 +162,7 @@ def test_cfg4_model_at_its_launch_shapes():
     T.tasc_verify_step(rig.model, rig.session, drafts_d, cfg.k, None, None, logits)
     got = logits[b].cpu().numpy().astype(np.float64)
     z = om.forward([int(before[-1])] + drafts_d[b].cpu().numpy().tolist(), cache)
-    _check_deep_model_logits("cfg4 model", got, z)
+    _check_deep_model_logits("cfg4", got, z)
 
 
 def test_cfg5_model_at_its_launch_shapes():
@@ -200,7 +203,7 @@ def test_cfg5_model_at_its_launch_shapes():
     T.tasc_verify_step(rig.model, rig.session, drafts_d, cfg.k, None, None, logits)
     got = logits[b].cpu().numpy().astype(np.float64)
     z = om.forward([int(before[-1])] + drafts_d[b].cpu().numpy().tolist(), cache)
-    _check_deep_model_logits("cfg5 model", got, z)
+    _check_deep_model_logits("cfg5", got, z)
 
 
 @pytest.mark.parametrize("name,mod,rem", [("cfg4", 64, 5), ("cfg5", 64, 37)])
@@ -230,7 +233,7 @@ def test_full_size_tables_and_drafts(name, mod, rem):
     # ---- drafts: a tiny target with the configuration's vocabulary carries the sequences; the tables are the real ones
     lazy = ON.LazyTables(tok, off, cfg.vocab, cfg.n_max, cfg.p_min)
     tiny = W.get_config("cfg1").scaled(vocab=cfg.vocab, n_max=cfg.n_max, batch=16, prompt_len=160, gen_len=8, k=cfg.k)
-    weights = W.make_model(tiny)
+    weights = W.make_model(tiny, (tok, off))       # corpus-biased LM head: the committed first token continues the corpus text
     max_len = 160 + 8 + 32
     model = T.tasc_model_create(tiny, weights, max_len)
     sess = T.tasc_session_create(model, tiny.batch, max_len, 16)

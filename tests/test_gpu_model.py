@@ -179,9 +179,9 @@ def test_api_errors():
 
 @pytest.mark.parametrize("heads", [(6, 2, 32), (4, 2, 64), (2, 1, 128), (4, 4, 64)])
 def test_small_batch_fused_kernel(heads):
-    """bf16 forwards of at most 16 rows run in the fused persistent kernel: against the oracle, against the
-    same kernel launched phase by phase and with agent-scope barriers only (bit-identical), and speculative ==
-    greedy within each mode."""
+    """bf16 forwards of at most 16 rows run in one persistent launch per step: the spatial-pipeline kernel (modes 5 and,
+    launched phase by phase, 6) and the barrier kernel (modes 2, 3, 4, and 1 phase by phase) against the oracle and
+    against each other (bit-identical), and speculative == greedy within each mode."""
     import torch
     import paper_2602_24174_amd as T
     from gpu_util import Rig
@@ -199,10 +199,12 @@ def test_small_batch_fused_kernel(heads):
     om = OM.OracleModel(cfg, rig.weights)
     results = {}
     try:
-        # 3 = persistent kernel with agent-scope barriers only, 4 = half of the layer group prefetching
-        for mode in (2, 3, 4, 1, 0):
+        # barrier kernel: 2 = persistent, 3 = agent-scope barriers only, 4 = half of the layer group prefetching, 1 = one
+        # launch per phase; pipeline kernel: 5 = persistent (the default), 6 = one launch per phase; 0 = generic kernels
+        for mode in (5, 6, 2, 3, 4, 1, 0):
             print(f"heads {heads} mode {mode}", flush=True)
-            T.tasc_config_set(T.TASC_CFG_SMALL_PATH, min(mode, 2))
+            T.tasc_config_set(T.TASC_CFG_SMALL_KERNEL, 1 if mode in (5, 6) else 0)
+            T.tasc_config_set(T.TASC_CFG_SMALL_PATH, {5: 2, 6: 1}.get(mode, min(mode, 2)))
             T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 0 if mode == 3 else 1)
             T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WORKERS, 16 if mode == 4 else 0)
             out, st, tr = rig.generate(trace_steps=cfg.gen_len)
@@ -234,20 +236,19 @@ def test_small_batch_fused_kernel(heads):
                     after = T.tasc_session_get_tokens(rig.session, b)
                     caches[b].length += len(after) - len(before[b])
             print(f"mode {mode}: max |logit - oracle| = {worst:.3e}, steps {st.steps}, XCD-local steps {st.xcd_local_steps}", flush=True)
-            if mode in (2, 4):
-                assert st.xcd_local_steps > 0, "the layer group was expected to run on one XCD"
-            if mode == 3:
+            if mode in (3, 5, 6):
                 assert st.xcd_local_steps == 0
             assert worst <= 5e-2
             results[mode] = (out, tr, np.stack(all_logits))
     finally:
+        T.tasc_config_set(T.TASC_CFG_SMALL_KERNEL, 1)
         T.tasc_config_set(T.TASC_CFG_SMALL_PATH, 2)
         T.tasc_config_set(T.TASC_CFG_SMALL_XCD_LOCAL, 1)
         T.tasc_config_set(T.TASC_CFG_SMALL_LAYER_WORKERS, 0)
-    for other in (1, 3, 4):
-        assert (results[other][0] == results[2][0]).all() and (results[other][1] == results[2][1]).all()
-        assert (results[other][2] == results[2][2]).all(), "persistent (XCD-local or agent-scope barriers) and " \
-            "per-phase launches must be bit-identical"
+    for other in (6, 2, 1, 3, 4):
+        assert (results[other][0] == results[5][0]).all() and (results[other][1] == results[5][1]).all(), f"mode {other}"
+        assert (results[other][2] == results[5][2]).all(), f"mode {other}: the pipeline kernel, the barrier kernel (XCD-local " \
+            "or agent-scope barriers) and their per-phase launches must be bit-identical"
 
 
 @pytest.mark.parametrize("heads", [(4, 2, 64), (2, 1, 128), (6, 2, 32)])
