@@ -173,3 +173,31 @@ def test_drafts_wide_keys_match_oracle(lam):
             matched_high += m is not None and m[0] >= 4
     if lam > 0:
         assert matched_high > 0, "no sequence reached a corpus context of 3+ tokens: the wide keys went untested"
+
+
+def test_drafts_long_single_token_run():
+    """A sequence that is one token repeated 3,900 times (every position matches the suffix at every order: the longest
+    successor list a sequence can have), one that alternates two tokens, and one long copy of corpus text: drafts equal
+    the oracle's."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    cfg = W.get_config("cfg1").scaled(batch=3, gen_len=8, prompt_len=3900, n_max=4)
+    rig = Rig(cfg, max_rows=64)
+    tok, off = rig.corpus
+    ref = ON.build_tables_flat(tok, off, cfg.vocab, cfg.n_max, cfg.p_min)
+    prompts = [np.full(3900, 11, dtype=np.int32), np.tile(np.array([5, 9], dtype=np.int32), 1950),
+               np.tile(tok[off[3]:off[4]], 80)[:3900].astype(np.int32)]
+    flat = np.concatenate(prompts)
+    poff = np.cumsum([0] + [len(p) for p in prompts]).astype(np.int64)
+    T.tasc_session_prefill(rig.model, rig.session, flat, poff, cfg.gen_len)
+    for lam, p_min_ctx in ((49152, 1), (0, 1), (32768, 3000)):
+        for k in (1, 8):
+            drafts = torch.zeros((cfg.batch, k), dtype=torch.int32, device="cuda")
+            T.tasc_draft(rig.ng, rig.session, T.spec_params(k, lam, p_min_ctx, 1), drafts)
+            got = drafts.cpu().numpy()
+            for b in range(cfg.batch):
+                committed = T.tasc_session_get_tokens(rig.session, b)
+                assert len(committed) == 3901
+                want = ON.draft(ref, committed, k, lam, p_min_ctx)
+                assert got[b].tolist() == want, f"lambda {lam} p_min_ctx {p_min_ctx} sequence {b} k {k}: {got[b].tolist()} vs {want}"
