@@ -209,6 +209,8 @@ def main():
     ap.add_argument("--others", default="cfg1,cfg2,cfg3,cfg4", help="workloads reported in per_config beside the headline ('' = none)")
     ap.add_argument("--low-accept", default="cfg3", help="workload that is also run with LM-head bias 1 (few drafts accepted; '' = none)")
     ap.add_argument("--cpu", type=int, default=1, help="1: time the CPU oracle on a bounded sample of the headline workload")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB plain copy kernel 4 times (the known-size reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} is not supported",
@@ -244,10 +246,17 @@ def main():
     head, corpus, weights, prompts = run_config(T, torch, W, cfg, args.steps, args.warmup)
     per_config.append(head)
     note("timed region done")
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            T.tasc_calibration_copy(dst, src, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
     cpu = None
     if args.cpu:
         note("CPU oracle sample")
-        cpu = cpu_baseline(W, cfg, corpus, weights, prompts, 8, 64)
+        cpu = cpu_baseline(W, cfg, corpus, weights, prompts, 16, 16)
         note("CPU oracle sample done")
 
     bf16 = cfg.dtype == "bf16"

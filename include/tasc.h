@@ -437,6 +437,18 @@ tasc_status tasc_calibration_mfma(int32_t iters, void* stream, double* tflops);
  * the published 8 TB/s for the kernels that stream weights and the KV cache.  Synchronises the stream. */
 tasc_status tasc_calibration_read(const void* src, size_t bytes, int32_t passes, void* stream, double* gbps);
 
+/* Latency of one hand-over of `bytes` among `n_workgroups` resident workgroups (ids stride * j of a grid of one workgroup
+ * per compute unit; the dispatcher deals ids to the 8 XCDs in turn, so stride 8 keeps them on one XCD and stride 1
+ * spreads them): every participant writes its share of the bytes, then reads all of them, 200 times in a row.
+ *   with_flags = 0  "flag in data": readers poll the data words themselves (agent-scope loads) until none holds the
+ *                   sentinel -- how the small-batch pipeline kernel hands activations from phase to phase;
+ *   with_flags = 1  stores, a wait for them, one arrival flag per participant polled by one wave, then the loads.
+ * *us_per_handover (HOST) = the best of three runs, from the device's 100 MHz clock.  The reference for how short a chain
+ * of dependent phases spread over many compute units can be.  Allocates and frees its buffers; synchronises the stream.
+ * Errors: TASC_EINVAL, TASC_EHIP (also when a wait times out or a reader sees stale data). */
+tasc_status tasc_calibration_handover(int32_t n_workgroups, int32_t stride, int32_t bytes, int32_t with_flags, void* stream,
+                                      double* us_per_handover);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,7 +4,9 @@ register-only MFMA loop.
     python -m paper_2602_24174_amd.calibrate
 
 Prints the copy kernel's rate over 1 GiB (read + write, best of 5), the read rates of tasc_calibration_read over 1 GiB
-(HBM), 128 MiB (memory-side cache) and 2 MiB (the L2 of every XCD), and the bf16 MFMA rate of tasc_calibration_mfma.
+(HBM), 128 MiB (memory-side cache) and 2 MiB (the L2 of every XCD), the bf16 MFMA rate of tasc_calibration_mfma, and
+the latency of one hand-over among resident workgroups (tasc_calibration_handover): polled data against arrival flags,
+on one XCD and across the chip, for the sizes the small-batch verify step hands from phase to phase.
 """
 import os
 import sys
@@ -37,6 +39,18 @@ def main():
     rates = [T.tasc_calibration_mfma(2000, stream) for _ in range(3)]
     print(f"MFMA loop, v_mfma_f32_32x32x16_bf16 on register operands, 8 waves per compute unit: {max(rates):.0f} TFLOP/s "
           f"(published dense bf16 peak 2500 TFLOP/s)")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    print("hand-over among resident workgroups, microseconds per hand-over (polled data | arrival flags, then loads):")
+    for label, n, stride in (("32 workgroups on one XCD", 32, 8), ("32 workgroups over all XCDs", 32, 1), ("96 workgroups over all XCDs", 96, 1),
+                             (f"all {cus} workgroups", cus, 1)):
+        if (n - 1) * stride >= cus:
+            continue
+        cells = []
+        for nbytes in (1024, 10240, 20480):
+            a = T.tasc_calibration_handover(n, stride, nbytes, False, stream)
+            b = T.tasc_calibration_handover(n, stride, nbytes, True, stream)
+            cells.append(f"{nbytes // 1024:2d} KB {a:5.2f} | {b:5.2f}")
+        print(f"  {label:32s} " + "   ".join(cells))
 
 
 if __name__ == "__main__":

@@ -206,3 +206,127 @@ extern "C" tasc_status tasc_calibration_copy(void* dst, const void* src, size_t 
     TASC_LAUNCH_CHECK();
     return TASC_OK;
 }
+
+// ---------------------------------------------------------------- hand-over latency between resident workgroups
+namespace {
+constexpr int kHandoverPhases = 200;
+constexpr unsigned kHandoverLds = 100 * 1024;      // forces one workgroup per compute unit: every participant is resident
+
+// `n_part` workgroups (ids stride * j) exchange `units` 8-byte words per phase, each writing its contiguous share and
+// then reading all of them.  mode 0: "flag in data" -- the words start as a sentinel, readers poll the words themselves
+// (agent-scope loads and stores) until none is the sentinel; three buffers are used in turn and an owner resets its
+// words once it has seen the next phase complete.  mode 1: the classic way -- data stored (agent scope), stores waited
+// for, one arrival flag per participant, one wave polls the flags, then the data is loaded.
+__global__ __launch_bounds__(512) void k_calibration_handover(u64* buf, u32* flags, int mode, int units, int stride, int n_part, u32* err, u64* ticks) {
+    const int wg = blockIdx.x;
+    if (wg % stride != 0 || wg / stride >= n_part) return;
+    const int r = wg / stride;
+    const int per = (units + n_part - 1) / n_part;
+    __shared__ u32 s_w[8];
+    u32 acc = 1;
+    u64 t0 = 0;
+    if (threadIdx.x == 0) t0 = wall_clock64();
+    for (int ph = 0; ph < kHandoverPhases; ++ph) {
+        u64* b = buf + (size_t)(mode == 0 ? ph % 3 : ph) * units;
+        u64* bprev = buf + (size_t)((ph + 2) % 3) * units;
+        for (int j = threadIdx.x; j < per; j += 512) {
+            const int u = r * per + j;
+            if (u < units) __hip_atomic_store(b + u, ((u64)(u32)ph << 32) | (acc & 0xFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (mode == 1) {
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            if (threadIdx.x < 64) {
+                if (threadIdx.x == 0) __hip_atomic_store(flags + r, (u32)(ph + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                u32 spins = 0;
+                for (int base = 0; base < n_part; base += 64) {
+                    for (;;) {
+                        u32 f = ph + 1;
+                        if (base + (int)threadIdx.x < n_part) f = __hip_atomic_load(flags + base + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (__all((int)(f - (u32)(ph + 1)) >= 0)) break;
+                        if (++spins > (1u << 16)) { atomicOr(err, 1u); break; }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        u32 mine = 0;
+        for (int u = threadIdx.x; u < units; u += 512) {
+            u64 v;
+            u32 spins = 0;
+            for (;;) {
+                v = __hip_atomic_load(b + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (mode == 1 || v != ~0ull) break;
+                if (++spins > (1u << 16)) { atomicOr(err, 1u); break; }
+            }
+            if ((u32)(v >> 32) != (u32)ph) atomicOr(err, 2u);          // stale or foreign data
+            mine += (u32)v;
+        }
+        for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+        if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = mine;
+        __syncthreads();
+        acc = s_w[0] + s_w[1] + s_w[2] + s_w[3] + s_w[4] + s_w[5] + s_w[6] + s_w[7];
+        if (mode == 0 && ph > 0)
+            for (int j = threadIdx.x; j < per; j += 512) {
+                const int u = r * per + j;
+                if (u < units) __hip_atomic_store(bprev + u, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        __syncthreads();
+        if (*(volatile u32*)err & 1u) break;
+    }
+    if (threadIdx.x == 0 && r == 0) { ticks[0] = wall_clock64() - t0; ticks[1] = acc; }
+}
+__global__ void k_calibration_fill(u64* p, size_t n, u64 v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+}  // namespace
+
+extern "C" tasc_status tasc_calibration_handover(int32_t n_workgroups, int32_t stride, int32_t bytes, int32_t with_flags, void* stream,
+                                                 double* us_per_handover) {
+    TASC_REQUIRE(us_per_handover && n_workgroups >= 2 && stride >= 1 && bytes >= 8 && bytes % 8 == 0 && bytes <= (1 << 20),
+                 "calibration_handover: 2 or more workgroups, stride >= 1 and 8 .. 2^20 bytes (a multiple of 8) needed");
+    hipStream_t st = (hipStream_t)stream;
+    int dev = 0, cus = 0;
+    TASC_HIP(hipGetDevice(&dev));
+    TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    TASC_REQUIRE((long)(n_workgroups - 1) * stride < cus, "calibration_handover: %d workgroups at stride %d do not fit %d compute units",
+                 n_workgroups, stride, cus);
+    static bool attr = false;
+    if (!attr) {
+        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_calibration_handover), hipFuncAttributeMaxDynamicSharedMemorySize, kHandoverLds));
+        attr = true;
+    }
+    const int units = bytes / 8, mode = with_flags ? 1 : 0;
+    const size_t words = (size_t)kHandoverPhases * units;
+    u64* buf = nullptr;
+    TASC_HIP(hipMalloc((void**)&buf, words * 8 + 4096 + 64));
+    u32* flags = reinterpret_cast<u32*>(buf + words);
+    u32* err = flags + 1024 - 16;
+    u64* ticks = reinterpret_cast<u64*>(flags + 1024);
+    double best = 1e30;
+    u32 herr = 0;
+    hipError_t e = hipSuccess;
+    for (int rep = 0; rep < 3 && e == hipSuccess && !herr; ++rep) {
+        k_calibration_fill<<<dim3(256), dim3(256), 0, st>>>(buf, words, ~0ull);
+        k_calibration_fill<<<dim3(1), dim3(256), 0, st>>>(reinterpret_cast<u64*>(flags), 512 + 8, 0ull);
+        k_calibration_handover<<<dim3(cus), dim3(512), kHandoverLds, st>>>(buf, flags, mode, units, stride, n_workgroups, err, ticks);
+        e = hipGetLastError();
+        u64 h[2] = {0, 0};
+        if (e == hipSuccess) e = hipMemcpyAsync(h, ticks, 16, hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipMemcpyAsync(&herr, err, 4, hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        const double us = (double)h[0] * 0.01 / kHandoverPhases;         // 100 MHz clock
+        if (us < best) best = us;
+    }
+    (void)hipFree(buf);
+    if (e != hipSuccess) {
+        tasc_set_error("calibration_handover: %s", hipGetErrorString(e));
+        return TASC_EHIP;
+    }
+    if (herr) {
+        tasc_set_error("calibration_handover: %s", (herr & 2u) ? "a reader saw stale data" : "a wait timed out (are all workgroups resident?)");
+        return TASC_EHIP;
+    }
+    *us_per_handover = best;
+    return TASC_OK;
+}

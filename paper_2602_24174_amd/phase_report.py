@@ -9,6 +9,7 @@ last end, and the barrier gap to the next phase.
 import argparse
 import os
 import sys
+import warnings
 
 import numpy as np
 
@@ -20,6 +21,7 @@ if ROOT not in sys.path:
 def pipeline_report(cfg, ts, n_wg):
     """Stamps of the spatial-pipeline kernel: per workgroup and phase (inputs complete, outputs stored); a workgroup
     only has stamps for the phases of its role."""
+    warnings.simplefilter("ignore", RuntimeWarning)              # phase 0 (the embedding) has no stamps: all-NaN columns
     L = cfg.n_layers
     have = ts[:, :, 1] > 0
     ready = np.where(have, ts[:, :, 0], np.nan)

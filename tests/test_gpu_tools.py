@@ -19,6 +19,12 @@ def test_calibration_copy_read_and_mfma():
     small, large = T.tasc_calibration_read(buf[:2 << 20], 512), T.tasc_calibration_read(buf, 8)
     print(f"read stream: 2 MiB {small:.0f} GB/s, 64 MiB {large:.0f} GB/s", flush=True)
     assert 500.0 < large < 40000.0 and small > large      # the L2-resident stream is the faster one
+    local, chip = T.tasc_calibration_handover(32, 8, 1024), T.tasc_calibration_handover(64, 1, 1024)
+    flags = T.tasc_calibration_handover(64, 1, 1024, True)
+    print(f"hand-over of 1 KB: 32 workgroups on one XCD {local:.2f} us, 64 over the chip {chip:.2f} us (with flags {flags:.2f} us)", flush=True)
+    assert 0.1 < local < 20.0 and 0.1 < chip < 50.0 and 0.1 < flags < 100.0
+    with pytest.raises(T.TascError):
+        T.tasc_calibration_handover(1, 1, 1024)            # needs two workgroups
     with pytest.raises(T.TascError):
         T.tasc_calibration_read(buf[:1000], 1)             # not a multiple of 64 KB
     with pytest.raises(T.TascError):
