@@ -319,11 +319,22 @@ tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* t
  *                        by barriers among a group of workgroups).  Results are bit-identical.
  *   TASC_CFG_PIPE_SHARE  output tiles (of 16 features) a workgroup of the spatial pipeline takes per layer at least, 1..3
  *                        (default 1): larger values put fewer workgroups on every role.  Results do not depend on it.
+ *   TASC_CFG_CHAINS      forwards of more than 16 rows: into how many ranges of sequences the batch is cut for the
+ *                        layers, each range on a stream of its own beside the caller's (0 = the library's rule, 1..4).
+ *                        A row's kernels and summation order do not depend on it, so neither does any result; with few
+ *                        rows per sequence range the layer kernels of one range leave compute units idle that another
+ *                        range's kernels fill.  The caller's stream waits for every range before the LM head.
+ *   TASC_CFG_STEP_GRAPH  1 (default): a verify step of the tiled kernels (forwards of more than 16 rows) is recorded
+ *                        into a HIP graph the second time it is called with the same k and the same draft / result
+ *                        pointers, and replayed as one graph launch from then on (a step is a few hundred launches
+ *                        with step-invariant arguments); 0: every kernel is launched on its own.  Same kernels, same
+ *                        results.  Steps that ask for logits or a trace, run under the per-class timers, or are
+ *                        called on a stream that is itself being captured are always launched one by one.
  */
 enum {
     TASC_CFG_SMALL_PATH = 0, TASC_CFG_SMALL_GRID = 1, TASC_CFG_SMALL_LAYER_WGS = 2, TASC_CFG_SMALL_LAYER_STRIDE = 3,
     TASC_CFG_TILED_PATH = 4, TASC_CFG_SMALL_XCD_LOCAL = 5, TASC_CFG_SMALL_LAYER_WORKERS = 6, TASC_CFG_SMALL_KERNEL = 7,
-    TASC_CFG_PIPE_SHARE = 8
+    TASC_CFG_PIPE_SHARE = 8, TASC_CFG_CHAINS = 9, TASC_CFG_STEP_GRAPH = 10
 };
 tasc_status tasc_config_set(int32_t key, int32_t value);
 

@@ -396,6 +396,8 @@ TASC_CFG_SMALL_XCD_LOCAL = 5
 TASC_CFG_SMALL_LAYER_WORKERS = 6
 TASC_CFG_SMALL_KERNEL = 7
 TASC_CFG_PIPE_SHARE = 8
+TASC_CFG_CHAINS = 9
+TASC_CFG_STEP_GRAPH = 10
 
 
 def tasc_config_set(key: int, value: int):

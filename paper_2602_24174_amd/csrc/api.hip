@@ -377,6 +377,8 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     s->barb_base = 0;
     s->ll_copy = 0;
     s->ll_armed = false;
+    s->chain_ready = false;
+    s->graph_st = nullptr;
     char* w = (char*)workspace;
     int i = 0;
     TascSessDev& d = s->d;
@@ -407,6 +409,31 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
     d.small_ws = (char*)(w + L.off[i++]);
     struct Guard { tasc_session* p; ~Guard() { if (p) tasc_session_destroy(p); } } guard{s};
     TASC_HIP(hipHostMalloc((void**)&s->host_counters, 32 * sizeof(u64), hipHostMallocDefault));
+    {   // streams (default priority) and events of the tiled forward's chains
+        int made_st = 0, made_ev = 0;
+        bool ok = hipEventCreateWithFlags(&s->chain_fork, hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; ok && i < TASC_MAX_CHAINS - 1; ++i) {
+            ok = hipStreamCreateWithFlags(&s->chain_st[i], hipStreamNonBlocking) == hipSuccess;
+            if (ok) ++made_st;
+            ok = ok && hipEventCreateWithFlags(&s->chain_join[i], hipEventDisableTiming) == hipSuccess;
+            if (ok) ++made_ev;
+        }
+        if (!ok) {
+            for (int i = 0; i < made_st; ++i) (void)hipStreamDestroy(s->chain_st[i]);
+            for (int i = 0; i < made_ev; ++i) (void)hipEventDestroy(s->chain_join[i]);
+            tasc_set_error("session_create: streams of the forward chains -> %s", hipGetErrorString(hipGetLastError()));
+            return TASC_EHIP;
+        }
+        if (hipStreamCreateWithFlags(&s->graph_st, hipStreamNonBlocking) != hipSuccess) {
+            s->graph_st = nullptr;
+            for (int i = 0; i < made_st; ++i) (void)hipStreamDestroy(s->chain_st[i]);
+            for (int i = 0; i < made_ev; ++i) (void)hipEventDestroy(s->chain_join[i]);
+            (void)hipEventDestroy(s->chain_fork);
+            tasc_set_error("session_create: capture stream -> %s", hipGetErrorString(hipGetLastError()));
+            return TASC_EHIP;
+        }
+        s->chain_ready = true;
+    }
     const int n = batch * s->max_blocks;
     k_init_block_tab<<<dim3((n + 255) / 256), dim3(256), 0, 0>>>(batch, s->max_blocks, d.block_tab);
     TASC_LAUNCH_CHECK();
@@ -422,6 +449,16 @@ extern "C" tasc_status tasc_session_create(const tasc_model* m, int32_t batch, i
 extern "C" void tasc_session_destroy(tasc_session* s) {
     if (!s) return;
     if (s->host_counters) (void)hipHostFree(s->host_counters);
+    for (TascStepGraph& e : s->step_graphs)
+        if (e.exec) (void)hipGraphExecDestroy(e.exec);
+    if (s->chain_ready) {
+        (void)hipStreamDestroy(s->graph_st);
+        (void)hipEventDestroy(s->chain_fork);
+        for (int i = 0; i < TASC_MAX_CHAINS - 1; ++i) {
+            (void)hipStreamDestroy(s->chain_st[i]);
+            (void)hipEventDestroy(s->chain_join[i]);
+        }
+    }
     delete s;
 }
 
@@ -495,11 +532,11 @@ extern "C" tasc_status tasc_session_prefill(const tasc_model* m, tasc_session* s
 }
 
 namespace {
-tasc_status verify_step_impl(const tasc_model* m, tasc_session* s, const int32_t* drafts, int32_t k, int32_t* accept_len,
-                             int32_t* emitted, float* logits_dbg, int32_t* trace_step, hipStream_t st) {
+// the launches of one verify step on `st`
+tasc_status verify_step_enqueue(const tasc_model* m, tasc_session* s, const int32_t* drafts, int32_t k, int32_t* accept_len,
+                                int32_t* emitted, float* logits_dbg, int32_t* trace_step, hipStream_t st) {
     const int B = s->batch, nq = k + 1;
     TascSessDev& d = s->d;
-    TascProfScope whole(TASC_KC_VERIFY, st);
     k_prepare_verify<<<dim3((B * nq + 255) / 256), dim3(256), 0, st>>>(B, k, s->max_len, m->desc.vocab, d.tokens, d.n_tok, d.cached,
                                                                        drafts, d.row_tok, d.n_rows, d.pos0, d.sel_rows, d.sel_tok);
     TASC_LAUNCH_CHECK();
@@ -513,6 +550,57 @@ tasc_status verify_step_impl(const tasc_model* m, tasc_session* s, const int32_t
     }
     TASC_LAUNCH_CHECK();
     return TASC_OK;
+}
+
+// A verify step of the tiled kernels is a few hundred launches whose arguments never change from step to step (row
+// counts, positions and tokens live in device memory), so the second step with the same arguments is recorded into a
+// graph, on a stream of the session's own, and every later one is a single graph launch on the caller's stream.
+tasc_status verify_step_impl(const tasc_model* m, tasc_session* s, const int32_t* drafts, int32_t k, int32_t* accept_len,
+                             int32_t* emitted, float* logits_dbg, int32_t* trace_step, hipStream_t st) {
+    TascProfScope whole(TASC_KC_VERIFY, st);
+    bool graphable = g_tasc_config.step_graph != 0 && s->chain_ready && !logits_dbg && !trace_step && !tasc_prof_any() &&
+                     tasc_forward_is_tiled(m, s, k + 1);
+    if (graphable) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+            (void)hipGetLastError();
+            graphable = false;                // the caller records this step itself
+        }
+    }
+    if (!graphable) return verify_step_enqueue(m, s, drafts, k, accept_len, emitted, logits_dbg, trace_step, st);
+    const int chains = tasc_forward_chains(m, s, k + 1);
+    TascStepGraph* g = nullptr;
+    for (TascStepGraph& e : s->step_graphs)
+        if (e.k == k && e.chains == chains && e.drafts == drafts && e.accept_len == accept_len && e.emitted == emitted) g = &e;
+    if (!g) {
+        if (s->step_graphs.size() >= 8) {     // a caller that keeps changing its buffers: forget the oldest
+            if (s->step_graphs.front().exec) (void)hipGraphExecDestroy(s->step_graphs.front().exec);
+            s->step_graphs.erase(s->step_graphs.begin());
+        }
+        s->step_graphs.push_back(TascStepGraph{k, chains, drafts, accept_len, emitted, 0, nullptr});
+        g = &s->step_graphs.back();
+    }
+    if (!g->exec && g->seen >= 1) {
+        hipGraph_t graph = nullptr;
+        bool ok = hipStreamBeginCapture(s->graph_st, hipStreamCaptureModeThreadLocal) == hipSuccess;
+        if (ok) {
+            const tasc_status rc = verify_step_enqueue(m, s, drafts, k, accept_len, emitted, nullptr, nullptr, s->graph_st);
+            ok = hipStreamEndCapture(s->graph_st, &graph) == hipSuccess && rc == TASC_OK && graph != nullptr;
+        }
+        ok = ok && hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0) == hipSuccess;
+        if (graph) (void)hipGraphDestroy(graph);
+        if (!ok) {
+            (void)hipGetLastError();
+            g->exec = nullptr;
+            g->seen = -1;                     // this key stays on plain launches
+        }
+    }
+    if (g->exec) {
+        TASC_HIP(hipGraphLaunch(g->exec, st));
+        return TASC_OK;
+    }
+    if (g->seen >= 0) ++g->seen;
+    return verify_step_enqueue(m, s, drafts, k, accept_len, emitted, logits_dbg, trace_step, st);
 }
 }  // namespace
 

@@ -13,7 +13,7 @@
 #include "kernels_tiled.h"
 
 TascConfig g_tasc_config = {/*small_path*/ 2, /*small_grid*/ 0, /*layer_wgs*/ 0, /*layer_stride*/ 0, /*tiled_path*/ 1, /*xcd_local*/ 1,
-                             /*layer_workers*/ 0, /*small_kernel*/ 1, /*pipe_share*/ 1};
+                             /*layer_workers*/ 0, /*small_kernel*/ 1, /*pipe_share*/ 1, /*chains*/ 0, /*step_graph*/ 1};
 static u64* g_phase_ts = nullptr;
 static int64_t g_phase_ts_cap = 0;
 
@@ -46,6 +46,12 @@ extern "C" tasc_status tasc_config_set(int32_t key, int32_t value) {
     } else if (key == TASC_CFG_SMALL_KERNEL) {
         TASC_REQUIRE(value == 0 || value == 1, "config_set: small kernel %d outside [0, 1]", value);
         g_tasc_config.small_kernel = value;
+    } else if (key == TASC_CFG_STEP_GRAPH) {
+        TASC_REQUIRE(value == 0 || value == 1, "config_set: step graph %d outside [0, 1]", value);
+        g_tasc_config.step_graph = value;
+    } else if (key == TASC_CFG_CHAINS) {
+        TASC_REQUIRE(value >= 0 && value <= TASC_MAX_CHAINS, "config_set: chains %d outside [0, %d]", value, TASC_MAX_CHAINS);
+        g_tasc_config.chains = value;
     } else if (key == TASC_CFG_PIPE_SHARE) {
         TASC_REQUIRE(value >= 1 && value <= 3, "config_set: pipeline share %d outside [1, 3]", value);
         g_tasc_config.pipe_share = value;
@@ -184,7 +190,7 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
         // 192-row tiles where they cover the rows with less padding and no more tiles (the tile shape never changes a
         // row's result)
         const int mt256 = (M + 255) / 256, mt192 = (M + 191) / 192;
-        if (EPI != TEPI_LMHEAD && mt192 <= mt256 && mt192 * 192 < mt256 * 256) {   // (the LM head's bias walk prefers 128-wide waves)
+        if (mt192 <= mt256 && mt192 * 192 < mt256 * 256) {
             dim3 g((unsigned)(mt192 * ((N + 255) / 256)), (unsigned)slices);
             k_gemm_tiled<EPI, TILE_MID><<<g, dim3(512), TG_LDS_BYTES(256, 192), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
             return;
@@ -205,6 +211,12 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
     }
 }
 
+// how many ranges of sequences run the layers side by side when the caller leaves the choice to the library
+int tiled_auto_chains(const tasc_model_desc& c, int batch, int nq) {
+    (void)c; (void)batch; (void)nq;
+    return 1;
+}
+
 tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
@@ -219,7 +231,7 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<4>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(128) + 4 * TA_MAX_BLOCKS));
         g_tiled_ready = true;
     }
-    const int M = s->batch * nq;
+    const int M_all = s->batch * nq;
     const int D = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim, F = c.d_ffn;
     const int nqkv = (H + 2 * Hkv) * hd, nqo = H * hd;
     KvGeom gm{H, Hkv, hd, nq, s->max_blocks, s->page_elems};
@@ -249,104 +261,146 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         ks = ks < TG_MAX_SLICES ? ks : TG_MAX_SLICES;
         return ks < 1 ? 1 : ks;
     };
-    // out (+)= A W^T through k-slices and the ordered reduction.  With `norm_g` the RMSNorm of the updated rows (gain
-    // norm_g, into d.h) is fused into the reduction; returns false if the caller still has to run it (no slices).
-    auto gemm_sliced = [&](const BF16* A, const void* Wm, int N, int K, float* out, bool resid, const float* norm_g) {
-        const int ks = slices(N, K);
-        if (ks == 1) {
-            if (resid) launch_gemm<TEPI_RESID>(A, Wm, M, N, K, out, nullptr, none, 1, st);
-            else launch_gemm<TEPI_STORE>(A, Wm, M, N, K, out, nullptr, none, 1, st);
-            return false;
-        }
-        launch_gemm<TEPI_PARTIAL>(A, Wm, M, N, K, d.att_part, nullptr, none, ks, st);
-        const size_t mn = (size_t)M * N;
-        if (resid && norm_g && N == D && D <= RRN_MAX_D) {
-            bool fused = true;
-            switch (ks) {
-#define RRN_CASE(NS) case NS: k_reduce_resid_norm<NS><<<dim3(M), dim3(256), 0, st>>>(d.att_part, mn, out, norm_g, D, c.rms_eps, (BF16*)d.h); break;
-                RRN_CASE(2) RRN_CASE(3) RRN_CASE(4) RRN_CASE(5) RRN_CASE(6) RRN_CASE(7) RRN_CASE(8)
-#undef RRN_CASE
-                default: fused = false;
-            }
-            if (fused) return true;
-        }
-        const unsigned blocks = (unsigned)((mn / 4 + 255) / 256);
-        if (resid) k_splitk_reduce<true><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
-        else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(d.att_part, ks, mn, out);
-        return false;
-    };
     int att_chunks = 512 / (s->batch * Hkv);          // two workgroups per compute unit in one round,
     att_chunks = att_chunks < 1 ? 1 : (att_chunks > 4 ? 4 : att_chunks);   // but no more than 4 partial results to merge
-    const int rows_pass = 32;
-    const dim3 attn_grid(s->batch * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
     {
         PROF(TASC_KC_PREPARE);
-        k_embed<BF16><<<dim3(M), dim3(64), 0, st>>>((const BF16*)m->embed, d.row_tok, D, d.x);
+        k_embed<BF16><<<dim3(M_all), dim3(64), 0, st>>>((const BF16*)m->embed, d.row_tok, D, d.x);
     }
     TASC_LAUNCH_CHECK();
-    bool h_ready = false;                 // d.h already holds the layer's normalised input
-    for (int l = 0; l < c.n_layers; ++l) {
-        const TascLayerW& w = m->layers[l];
-        BF16* kv_layer = (BF16*)s->kv_pool + (size_t)l * s->kv_layer_stride;
-        if (!h_ready) {
-            PROF(TASC_KC_NORM);
-            if (D <= RRN_MAX_D) k_rmsnorm_row<<<dim3(M), dim3(256), 0, st>>>(d.x, w.g1, D, c.rms_eps, (BF16*)d.h);
-            else k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g1, nullptr, D, c.rms_eps, (BF16*)d.h);
-        }
-        const int ks_qkv = slices(nqkv, D);
-        {
-            PROF(TASC_KC_GEMM_QKV);
-            if (ks_qkv == 1) launch_gemm<TEPI_STORE>((const BF16*)d.h, w.wqkv, M, nqkv, D, d.qkv, nullptr, none, 1, st);
-            else launch_gemm<TEPI_PARTIAL>((const BF16*)d.h, w.wqkv, M, nqkv, D, d.att_part, nullptr, none, ks_qkv, st);
-        }
-        {
-            // the k-slices of a split projection are added inside the rotation kernel (same order as the reduction kernel)
-            PROF(TASC_KC_ROPE_KV);
-            k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(ks_qkv == 1 ? d.qkv : d.att_part, m->rope_cos, m->rope_sin, c.max_pos, d.n_rows,
-                                                         d.pos0, d.block_tab, gm, (BF16*)d.q, kv_layer, ks_qkv, (size_t)M * nqkv);
-        }
-        {
-            PROF(TASC_KC_ATTN);
-            AttnArgs aa{(const BF16*)d.q, (BF16*)d.att, kv_layer, d.n_rows, d.pos0, d.block_tab, s->batch, nq, H, Hkv,
-                        s->max_blocks, s->page_elems, 1.0f / sqrtf((float)hd)};
-            if (hd == 32 || s->max_blocks > TA_MAX_BLOCKS) {
-                if (hd == 64) k_attn_tiled<2><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
-                else if (hd == 128) k_attn_tiled<4><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
-                else k_attn_tiled<1><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
-            } else {
-                // keys and values staged in LDS, 64 rows per pass; the key tiles are dealt to att_chunks workgroups, a
-                // number fixed by the session's batch (it sets the order in which a row's keys are added)
-                const size_t rows_all = (size_t)M;
-                AttnStagedArgs sa{aa, d.att_part, d.att_part + (size_t)att_chunks * rows_all * H * hd, att_chunks};
-                const dim3 grid(s->batch * Hkv, (nq * (H / Hkv) + 63) / 64, att_chunks);
-                if (hd == 64) k_attn_staged<2><<<grid, dim3(SMALL_THREADS), TA_LDS_BYTES(64) + 4 * s->max_blocks, st>>>(sa);
-                else k_attn_staged<4><<<grid, dim3(SMALL_THREADS), TA_LDS_BYTES(128) + 4 * s->max_blocks, st>>>(sa);
-                if (att_chunks > 1) {
-                    const size_t n = rows_all * H * hd / 4;
-                    k_attn_merge<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(sa.part_o, sa.part_ml, att_chunks, rows_all, H, hd, (BF16*)d.att);
+
+    // The layers of sequences [b0, b0 + nb) on stream `st`: every kernel below computes a row from that row's own data
+    // (and its sequence's cache), in an order fixed by the session, so the layers may run for several ranges of
+    // sequences side by side ("chains", each on a stream of its own with its own share of every buffer) without
+    // changing a bit of any row.
+    auto run_layers = [&](int b0, int nb, hipStream_t st) -> tasc_status {
+        const int M = nb * nq;
+        const size_t r0 = (size_t)b0 * nq;
+        float* const x = d.x + r0 * D;
+        BF16* const h = (BF16*)d.h + r0 * D;
+        float* const qkv = d.qkv + r0 * nqkv;
+        BF16* const q = (BF16*)d.q + r0 * nqo;
+        BF16* const att = (BF16*)d.att + r0 * nqo;
+        BF16* const act = (BF16*)d.act + r0 * F;
+        float* const part = d.att_part + r0 * 8 * (size_t)(nqkv > D ? nqkv : D);   // the scratch is sized per row
+        const int32_t* const n_rows = d.n_rows + b0;
+        const int32_t* const pos0 = d.pos0 + b0;
+        const int32_t* const block_tab = d.block_tab + (size_t)b0 * s->max_blocks;
+        // out (+)= A W^T through k-slices and the ordered reduction.  With `norm_g` the RMSNorm of the updated rows (gain
+        // norm_g, into h) is fused into the reduction; returns false if the caller still has to run it (no slices).
+        auto gemm_sliced = [&](const BF16* A, const void* Wm, int N, int K, float* out, bool resid, const float* norm_g) {
+            const int ks = slices(N, K);
+            if (ks == 1) {
+                if (resid) launch_gemm<TEPI_RESID>(A, Wm, M, N, K, out, nullptr, none, 1, st);
+                else launch_gemm<TEPI_STORE>(A, Wm, M, N, K, out, nullptr, none, 1, st);
+                return false;
+            }
+            launch_gemm<TEPI_PARTIAL>(A, Wm, M, N, K, part, nullptr, none, ks, st);
+            const size_t mn = (size_t)M * N;
+            if (resid && norm_g && N == D && D <= RRN_MAX_D) {
+                bool fused = true;
+                switch (ks) {
+#define RRN_CASE(NS) case NS: k_reduce_resid_norm<NS><<<dim3(M), dim3(256), 0, st>>>(part, mn, out, norm_g, D, c.rms_eps, h); break;
+                    RRN_CASE(2) RRN_CASE(3) RRN_CASE(4) RRN_CASE(5) RRN_CASE(6) RRN_CASE(7) RRN_CASE(8)
+#undef RRN_CASE
+                    default: fused = false;
+                }
+                if (fused) return true;
+            }
+            const unsigned blocks = (unsigned)((mn / 4 + 255) / 256);
+            if (resid) k_splitk_reduce<true><<<dim3(blocks), dim3(256), 0, st>>>(part, ks, mn, out);
+            else k_splitk_reduce<false><<<dim3(blocks), dim3(256), 0, st>>>(part, ks, mn, out);
+            return false;
+        };
+        const int rows_pass = 32;
+        const dim3 attn_grid(nb * Hkv, (nq * (H / Hkv) + rows_pass - 1) / rows_pass);
+        bool h_ready = false;                 // h already holds the layer's normalised input
+        for (int l = 0; l < c.n_layers; ++l) {
+            const TascLayerW& w = m->layers[l];
+            BF16* kv_layer = (BF16*)s->kv_pool + (size_t)l * s->kv_layer_stride;
+            if (!h_ready) {
+                PROF(TASC_KC_NORM);
+                if (D <= RRN_MAX_D) k_rmsnorm_row<<<dim3(M), dim3(256), 0, st>>>(x, w.g1, D, c.rms_eps, h);
+                else k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(x, w.g1, nullptr, D, c.rms_eps, h);
+            }
+            const int ks_qkv = slices(nqkv, D);
+            {
+                PROF(TASC_KC_GEMM_QKV);
+                if (ks_qkv == 1) launch_gemm<TEPI_STORE>(h, w.wqkv, M, nqkv, D, qkv, nullptr, none, 1, st);
+                else launch_gemm<TEPI_PARTIAL>(h, w.wqkv, M, nqkv, D, part, nullptr, none, ks_qkv, st);
+            }
+            {
+                // the k-slices of a split projection are added inside the rotation kernel (same order as the reduction kernel)
+                PROF(TASC_KC_ROPE_KV);
+                k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(ks_qkv == 1 ? qkv : part, m->rope_cos, m->rope_sin, c.max_pos, n_rows,
+                                                             pos0, block_tab, gm, q, kv_layer, ks_qkv, (size_t)M * nqkv);
+            }
+            {
+                PROF(TASC_KC_ATTN);
+                AttnArgs aa{q, att, kv_layer, n_rows, pos0, block_tab, nb, nq, H, Hkv,
+                            s->max_blocks, s->page_elems, 1.0f / sqrtf((float)hd)};
+                if (hd == 32 || s->max_blocks > TA_MAX_BLOCKS) {
+                    if (hd == 64) k_attn_tiled<2><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+                    else if (hd == 128) k_attn_tiled<4><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+                    else k_attn_tiled<1><<<attn_grid, dim3(SMALL_THREADS), 0, st>>>(aa);
+                } else {
+                    // keys and values staged in LDS, 64 rows per pass; the key tiles are dealt to att_chunks workgroups, a
+                    // number fixed by the session's batch (it sets the order in which a row's keys are added)
+                    const size_t rows_all = (size_t)M;
+                    AttnStagedArgs sa{aa, part, part + (size_t)att_chunks * rows_all * H * hd, att_chunks};
+                    const dim3 grid(nb * Hkv, (nq * (H / Hkv) + 63) / 64, att_chunks);
+                    if (hd == 64) k_attn_staged<2><<<grid, dim3(SMALL_THREADS), TA_LDS_BYTES(64) + 4 * s->max_blocks, st>>>(sa);
+                    else k_attn_staged<4><<<grid, dim3(SMALL_THREADS), TA_LDS_BYTES(128) + 4 * s->max_blocks, st>>>(sa);
+                    if (att_chunks > 1) {
+                        const size_t n = rows_all * H * hd / 4;
+                        k_attn_merge<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(sa.part_o, sa.part_ml, att_chunks, rows_all, H, hd, att);
+                    }
                 }
             }
+            bool normed;
+            {
+                PROF(TASC_KC_GEMM_O);
+                normed = gemm_sliced(att, w.wo, D, nqo, x, true, w.g2);
+            }
+            if (!normed) {
+                PROF(TASC_KC_NORM);
+                if (D <= RRN_MAX_D) k_rmsnorm_row<<<dim3(M), dim3(256), 0, st>>>(x, w.g2, D, c.rms_eps, h);
+                else k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(x, w.g2, nullptr, D, c.rms_eps, h);
+            }
+            {
+                PROF(TASC_KC_GEMM_GU);
+                launch_gemm<TEPI_SWIGLU>(h, w.wgu, M, 2 * F, D, nullptr, act, none, 1, st);
+            }
+            {
+                // the next layer's first RMSNorm rides on this reduction
+                PROF(TASC_KC_GEMM_D);
+                h_ready = gemm_sliced(act, w.wd, D, F, x, true, l + 1 < c.n_layers ? m->layers[l + 1].g1 : nullptr);
+            }
+            TASC_LAUNCH_CHECK();
         }
-        bool normed;
-        {
-            PROF(TASC_KC_GEMM_O);
-            normed = gemm_sliced((const BF16*)d.att, w.wo, D, nqo, d.x, true, w.g2);
+        return TASC_OK;
+    };
+
+    // chains: few rows leave the layer kernels short of workgroups and bound by their own start-up and dependent
+    // memory round trips; ranges of sequences that run side by side fill the compute units.  Each reads the weights
+    // again (from the caches when the chains keep pace), so the count stays small.
+    const int chains = tasc_forward_chains(m, s, nq);
+    if (chains <= 1) {
+        const tasc_status rc = run_layers(0, s->batch, st);
+        if (rc != TASC_OK) return rc;
+    } else {
+        TASC_HIP(hipEventRecord(s->chain_fork, st));
+        for (int ch = 0; ch < chains; ++ch) {
+            const int b0 = (int)((long)s->batch * ch / chains), b1 = (int)((long)s->batch * (ch + 1) / chains);
+            hipStream_t cs = ch == 0 ? st : s->chain_st[ch - 1];
+            if (ch > 0) TASC_HIP(hipStreamWaitEvent(cs, s->chain_fork, 0));
+            const tasc_status rc = run_layers(b0, b1 - b0, cs);
+            if (rc != TASC_OK) return rc;
+            if (ch > 0) {
+                TASC_HIP(hipEventRecord(s->chain_join[ch - 1], cs));
+                TASC_HIP(hipStreamWaitEvent(st, s->chain_join[ch - 1], 0));
+            }
         }
-        if (!normed) {
-            PROF(TASC_KC_NORM);
-            if (D <= RRN_MAX_D) k_rmsnorm_row<<<dim3(M), dim3(256), 0, st>>>(d.x, w.g2, D, c.rms_eps, (BF16*)d.h);
-            else k_rmsnorm<BF16><<<dim3(M), dim3(64), 0, st>>>(d.x, w.g2, nullptr, D, c.rms_eps, (BF16*)d.h);
-        }
-        {
-            PROF(TASC_KC_GEMM_GU);
-            launch_gemm<TEPI_SWIGLU>((const BF16*)d.h, w.wgu, M, 2 * F, D, nullptr, (BF16*)d.act, none, 1, st);
-        }
-        {
-            // the next layer's first RMSNorm rides on this reduction
-            PROF(TASC_KC_GEMM_D);
-            h_ready = gemm_sliced((const BF16*)d.act, w.wd, D, F, d.x, true, l + 1 < c.n_layers ? m->layers[l + 1].g1 : nullptr);
-        }
-        TASC_LAUNCH_CHECK();
     }
     if (n_sel > 0) {
         {
@@ -633,6 +687,20 @@ tasc_status tasc_pipe_arm(tasc_session* s, hipStream_t st) {
     TASC_LAUNCH_CHECK();
     s->ll_armed = true;
     return TASC_OK;
+}
+
+int tasc_forward_chains(const tasc_model* m, const tasc_session* s, int32_t nq) {
+    int chains = g_tasc_config.chains > 0 ? g_tasc_config.chains : tiled_auto_chains(m->desc, s->batch, nq);
+    chains = chains < s->batch ? chains : s->batch;
+    chains = chains < TASC_MAX_CHAINS ? chains : TASC_MAX_CHAINS;
+    if (tasc_prof_any() || !s->chain_ready) chains = 1;       // the per-class timers bracket launches on one stream
+    return chains;
+}
+
+bool tasc_forward_is_tiled(const tasc_model* m, const tasc_session* s, int32_t nq) {
+    const int decode_rows = s->max_rows < SMALL_ROWS ? s->max_rows : SMALL_ROWS;
+    if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m, s->batch, decode_rows, s->max_blocks)) return false;
+    return g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc);
 }
 
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel, float* logits_dbg,

@@ -145,7 +145,8 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
     // memory for the step after that (activations at ka, weights at kw; steps past the last re-read the last one and
     // are never multiplied).  The LDS stores and the fetches so travel under the step's MFMAs instead of ahead of them.
     // Nothing sits under a condition: a conditional load ends in a register copy at the join, which waits for the data.
-    static_assert(PW <= 4 && PA <= 4 && TG_BK == 64, "the refill is split in four quarters, one per MFMA k-block");
+    static_assert(TG_BK == 64, "the refill is split in four quarters, one per MFMA k-block");
+    constexpr int QW = (PW + 3) / 4, QA = (PA + 3) / 4;    // staging passes per quarter
     auto step = [&](int buf, StageW& w, StageA& sa_, int ka, int kw) __attribute__((always_inline)) {
         const uint16_t* bw = sW + (size_t)(buf * BN + wn * SN + (lane & 31)) * TG_LD + 8 * (lane >> 5);
         const uint16_t* ba = sA + (size_t)(buf * BM + wm * SM + (lane & 31)) * TG_LD + 8 * (lane >> 5);
@@ -158,10 +159,18 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
             for (int i = 0; i < TI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(bw + (size_t)i * 32 * TG_LD + ks * 16);
 #pragma unroll
             for (int j = 0; j < TJ; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(ba + (size_t)j * 32 * TG_LD + ks * 16);
-            if (ks < PW) *reinterpret_cast<u32x4*>(dw + (size_t)ks * ROWS_PASS * TG_LD) = w.w[ks];      // compile-time conditions
-            if (ks < PA) *reinterpret_cast<u32x4*>(da + (size_t)ks * ROWS_PASS * TG_LD) = sa_.a[ks];
-            if (ks < PA) sa_.a[ks] = *reinterpret_cast<const u32x4*>(abase + aoff[ks] + ka);
-            if (ks < PW) w.w[ks] = *reinterpret_cast<const u32x4*>(wbase + woff[ks] + kw);
+#pragma unroll
+            for (int t = 0; t < QW; ++t)                                                              // compile-time conditions
+                if (ks * QW + t < PW) *reinterpret_cast<u32x4*>(dw + (size_t)(ks * QW + t) * ROWS_PASS * TG_LD) = w.w[ks * QW + t];
+#pragma unroll
+            for (int t = 0; t < QA; ++t)
+                if (ks * QA + t < PA) *reinterpret_cast<u32x4*>(da + (size_t)(ks * QA + t) * ROWS_PASS * TG_LD) = sa_.a[ks * QA + t];
+#pragma unroll
+            for (int t = 0; t < QA; ++t)
+                if (ks * QA + t < PA) sa_.a[ks * QA + t] = *reinterpret_cast<const u32x4*>(abase + aoff[ks * QA + t] + ka);
+#pragma unroll
+            for (int t = 0; t < QW; ++t)
+                if (ks * QW + t < PW) w.w[ks * QW + t] = *reinterpret_cast<const u32x4*>(wbase + woff[ks * QW + t] + kw);
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
@@ -216,7 +225,8 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
             float best = -INFINITY;
             int32_t best_i = 0x7FFFFFFF;
             const float base = lm_base[j];
-            if (lm.bias.rowptr) {
+            // (most 32-row blocks have no seen successor inside the wave's span: then there is nothing to patch)
+            if (lm.bias.rowptr && __ballot(lm_cur[j] < lm_end[j]) != 0) {
                 for (int q = lane; q < 32 * LDP; q += 64) patch[q] = 0.f;
                 __builtin_amdgcn_wave_barrier();
                 const int lo = n0 + SN * wn;
@@ -281,41 +291,77 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
         }
         return;
     }
+    // A lane holds runs of 4 features of 32 different rows, so a direct store would write 16-byte pieces of 32 rows per
+    // instruction.  Each wave turns its block around in LDS instead (the tile buffers are free after the loop's last
+    // barrier; a region of its own per wave and 32-row block, so waves do not wait for each other): written as
+    // [row][feature], read back with consecutive lanes on consecutive 16-byte chunks of one row, so that every store
+    // instruction covers whole rows of the wave's block (128 to 512 contiguous bytes each).
+    if (EPI == TEPI_SWIGLU) {
+        // rows 0..15 of a 32-feature tile are gate features, rows 16..31 the up rows of the same features: SN / 2 outputs
+        constexpr int OW = SN / 2;                          // outputs per row of the wave's block (bf16)
+        constexpr int LDO = OW * 2 + 16;                    // padded row (bytes)
+        constexpr int CH = OW * 2 / 16;                     // 16-byte chunks per row
+        constexpr int RPP = 64 / CH;                        // rows per read pass
+        static_assert((size_t)WN * WM * TJ * 32 * LDO <= TG_LDS_BYTES(BN, BM) && 64 % CH == 0 && 32 % RPP == 0, "epilogue staging fits the tile buffers");
+        unsigned char* reg = lds + (size_t)wave * TJ * 32 * LDO;
+        const int Nh = N / 2, fwave = (n0 + SN * wn) / 2;
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-        const int m = m0 + SM * wm + 32 * j + (lane & 31);
-        if (m >= M) continue;
+        for (int j = 0; j < TJ; ++j) {
+            unsigned char* rj = reg + (size_t)j * 32 * LDO;
 #pragma unroll
-        for (int i = 0; i < TI; ++i) {
-            if (EPI == TEPI_SWIGLU) {
-                // rows 0..15 of the 32-row tile are gate features, rows 16..31 the up rows of the same features
-                const int fbase = (n0 + SN * wn + 32 * i) / 2;
+            for (int i = 0; i < TI; ++i)
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
-                    const int f = fbase + 8 * q + 4 * (lane >> 5);
-                    if (2 * f < N) {
-                        float o[4];
+                    float o[4];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const float g = acc[i][j][4 * q + u], up = acc[i][j][8 + 4 * q + u];
-                            o[u] = g / (1.0f + __expf(-g)) * up;
-                        }
-                        *reinterpret_cast<u32x2*>(outb + (size_t)m * (N / 2) + f) = pack_bf16x4(o[0], o[1], o[2], o[3]);
+                    for (int u = 0; u < 4; ++u) {
+                        const float g = acc[i][j][4 * q + u], up = acc[i][j][8 + 4 * q + u];
+                        o[u] = g / (1.0f + __expf(-g)) * up;
                     }
+                    *reinterpret_cast<u32x2*>(rj + (size_t)(lane & 31) * LDO + (16 * i + 8 * q + 4 * (lane >> 5)) * 2) = pack_bf16x4(o[0], o[1], o[2], o[3]);
                 }
-            } else {
+        }
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + SN * wn + 32 * i + 8 * q + 4 * (lane >> 5);
-                    if (n < N) {
-                        float4* p = reinterpret_cast<float4*>(outf + (size_t)m * N + n);
-                        float4 vv = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                        if (EPI == TEPI_RESID) {
-                            const float4 old = *p;
-                            vv.x += old.x; vv.y += old.y; vv.z += old.z; vv.w += old.w;
-                        }
-                        *p = vv;
+        for (int j = 0; j < TJ; ++j) {
+            const unsigned char* rj = reg + (size_t)j * 32 * LDO;
+#pragma unroll
+            for (int p = 0; p < 32 / RPP; ++p) {
+                const int r = p * RPP + lane / CH, ch = lane % CH;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(rj + (size_t)r * LDO + ch * 16);
+                const int m = m0 + SM * wm + 32 * j + r, f = fwave + ch * 8;
+                if (m < M && f < Nh) *reinterpret_cast<u32x4*>(outb + (size_t)m * Nh + f) = v;
+            }
+        }
+    } else {
+        constexpr int LDO = SN * 4 + 16;                    // padded row of the wave's block (bytes, fp32)
+        constexpr int CH = SN * 4 / 16;
+        constexpr int RPP = 64 / CH;
+        static_assert((size_t)WN * WM * 32 * LDO <= TG_LDS_BYTES(BN, BM) && 64 % CH == 0 && 32 % RPP == 0, "epilogue staging fits the tile buffers");
+        unsigned char* reg = lds + (size_t)wave * 32 * LDO;
+        const int nwave = n0 + SN * wn;
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            if (j > 0) __builtin_amdgcn_wave_barrier();     // the reads of the block before are done (LDS serves a wave in order)
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(reg + (size_t)(lane & 31) * LDO + (32 * i + 8 * q + 4 * (lane >> 5)) * 4) =
+                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int p = 0; p < 32 / RPP; ++p) {
+                const int r = p * RPP + lane / CH, ch = lane % CH;
+                float4 vv = *reinterpret_cast<const float4*>(reg + (size_t)r * LDO + ch * 16);
+                const int m = m0 + SM * wm + 32 * j + r, n = nwave + ch * 4;
+                if (m < M && n < N) {
+                    float4* pp = reinterpret_cast<float4*>(outf + (size_t)m * N + n);
+                    if (EPI == TEPI_RESID) {
+                        const float4 old = *pp;
+                        vv.x += old.x; vv.y += old.y; vv.z += old.z; vv.w += old.w;
                     }
+                    *pp = vv;
                 }
             }
         }

@@ -12,6 +12,8 @@ std::vector<Pair> g_free;
 }  // namespace
 
 bool tasc_prof_on(int cls) { return (g_mask >> cls) & 1u; }
+// any class but the whole-step ones, whose brackets sit outside the step's launches
+bool tasc_prof_any() { return (g_mask & ~((1u << TASC_KC_VERIFY) | (1u << TASC_KC_DRAFT))) != 0; }
 
 int tasc_prof_begin(int cls, hipStream_t st) {
     std::lock_guard<std::mutex> lk(g_mu);

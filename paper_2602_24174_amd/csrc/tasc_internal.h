@@ -153,6 +153,7 @@ struct tasc_model {
 
 // ---------------------------------------------------------------- session
 #define TASC_KV_BLOCK 16
+#define TASC_MAX_CHAINS 4          // most ranges of sequences the tiled forward runs side by side
 #define TASC_DRAFT_MAX_LEN 4096   // longest sequence the draft kernel can hold in LDS
 #define TASC_LM_STRIP 128         // vocabulary columns per partial-argmax strip
 
@@ -189,6 +190,17 @@ struct TascSessDev {
     int32_t* bias_ptr;   // [M_max, n_strips + 1] LM-head bias cursors of the small-batch kernel
 };
 
+// one verify step of the tiled kernels, recorded once and replayed: its launches only name buffers of the session and
+// the caller's draft / result pointers, which make the key
+struct TascStepGraph {
+    int32_t k, chains;
+    const int32_t* drafts;
+    int32_t* accept_len;
+    int32_t* emitted;
+    int32_t seen;             // eager runs so far (the first run also does the kernels' one-off set-up); -1: capture failed
+    hipGraphExec_t exec;      // null until recorded
+};
+
 struct tasc_session {
     const tasc_model* model;
     int32_t batch, max_len, max_rows, max_blocks, n_strips;
@@ -201,6 +213,11 @@ struct tasc_session {
     u64* host_counters;       // pinned
     u32 bar_epoch;            // barriers the layer group's arrival flags (counters[32..63]) have seen so far
     u64 barb_base;            // same for the whole-grid barrier counter (counters[26])
+    hipStream_t chain_st[TASC_MAX_CHAINS - 1];   // streams of the second and later chains of the tiled forward
+    hipEvent_t chain_fork, chain_join[TASC_MAX_CHAINS - 1];
+    bool chain_ready;         // the streams and events above exist
+    hipStream_t graph_st;     // the stream verify steps are captured on (a graph may be launched on any stream)
+    std::vector<TascStepGraph> step_graphs;   // instantiated verify steps, by their arguments
     int ll_copy;              // which copy of the small-batch activation buffers the next pipeline launch uses
     bool ll_armed;            // both copies hold the "not written yet" pattern wherever the next launch expects it
 };
@@ -264,17 +281,24 @@ struct TascConfig {
     int layer_workers;        // members of the layer group that compute in XCD-local mode (0 = all), the rest prefetch
     int small_kernel;         // 1: the spatial-pipeline kernel where the model fits it, 0: the barrier kernel always
     int pipe_share;           // tiles a workgroup of the pipeline kernel takes per layer at least (1..3): fewer, fatter workgroups
+    int chains;               // ranges of sequences whose layers run side by side on streams of their own (0 = the library's rule)
+    int step_graph;           // 1: verify steps of the tiled kernels are recorded into a graph and replayed, 0: launched one by one
 };
 extern TascConfig g_tasc_config;
 
 // forward.hip
 // fills both copies of the small-batch activation buffers with the pipeline kernel's "not written yet" pattern
 tasc_status tasc_pipe_arm(tasc_session* s, hipStream_t st);
+// true if a forward of nq rows per sequence of this session takes the tiled kernels (and no fused persistent one)
+bool tasc_forward_is_tiled(const tasc_model* m, const tasc_session* s, int32_t nq);
+// the chain count forward_tiled would use
+int tasc_forward_chains(const tasc_model* m, const tasc_session* s, int32_t nq);
 tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, int32_t n_sel,
                               float* logits_dbg, TascVerifyTail* tail, hipStream_t st);
 
 // profile.hip: optional event timing per kernel class
 bool tasc_prof_on(int cls);
+bool tasc_prof_any();
 int tasc_prof_begin(int cls, hipStream_t st);
 void tasc_prof_end(int handle, hipStream_t st);
 struct TascProfScope {

@@ -27,6 +27,9 @@ def main():
     ap.add_argument("--docs", type=int, default=2000, help="corpus size (0 = the configuration's)")
     ap.add_argument("--steps", type=int, default=12)
     ap.add_argument("--max-rows", type=int, default=64, help="rows per sequence of a prompt chunk")
+    ap.add_argument("--chains", type=int, default=0, help="sequence ranges whose layers run side by side (0 = the library's rule)")
+    ap.add_argument("--graph", type=int, default=1, help="1: the step is recorded into a graph and replayed (the library's default), 0: plain launches")
+    ap.add_argument("--warm", type=int, default=0, help="untimed steps before the timed ones")
     args = ap.parse_args()
     import torch
     import workload as W
@@ -45,15 +48,25 @@ def main():
     T.tasc_session_prefill(model, session, prompts, prompt_off, cfg.gen_len)
     params = T.spec_params(cfg.k, cfg.lambda_q16, cfg.p_min_ctx, 1)
     drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
-    steps = min(args.steps, (cfg.gen_len - 1) // (cfg.k + 1))      # stay inside the session's generation budget
+    steps = min(args.steps, (cfg.gen_len - 1) // (cfg.k + 1) - args.warm)      # stay inside the session's generation budget
+    T.tasc_config_set(T.TASC_CFG_CHAINS, args.chains)
+    T.tasc_config_set(T.TASC_CFG_STEP_GRAPH, args.graph)
+    for _ in range(args.warm):
+        T.tasc_draft(table, session, params, drafts)
+        T.tasc_verify_step(model, session, drafts, cfg.k)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         T.tasc_draft(table, session, params, drafts)
         T.tasc_verify_step(model, session, drafts, cfg.k)
+    t_host = time.perf_counter() - t0
     torch.cuda.synchronize()
-    print(f"{cfg.name}: {steps} draft + verify steps of {cfg.batch} x {cfg.k + 1} rows, {(time.perf_counter() - t0) / steps * 1e3:.3f} ms per step "
-          f"(the first steps include one-off set-up of the kernels)", flush=True)
+    dt = time.perf_counter() - t0
+    import zlib
+    digest = zlib.crc32(b"".join(T.tasc_session_get_tokens(session, b).tobytes() for b in range(cfg.batch)))
+    print(f"{cfg.name}: {steps} draft + verify steps of {cfg.batch} x {cfg.k + 1} rows, chains {args.chains}, graph {args.graph}, {dt / steps * 1e3:.3f} ms per step, "
+          f"the host's share (enqueueing) {t_host / steps * 1e3:.3f} ms "
+          f"(without --warm the first steps include one-off set-up of the kernels); crc32 of all sequences' tokens {digest:08x}", flush=True)
 
 
 if __name__ == "__main__":

@@ -309,6 +309,53 @@ def test_tiled_mfma_kernels(heads):
         T.tasc_config_set(T.TASC_CFG_TILED_PATH, 1)
 
 
+def test_tiled_step_graph_and_chains():
+    """Verify steps of the tiled kernels replayed from a recorded graph, and the layers run as several chains of
+    sequences on streams of their own, give the tokens, accept lengths and counters of plain launches on one stream:
+    every replay is checked (the graph is recorded at the second step and replayed from then on, with host reads and
+    synchronisations between the steps), then whole generations."""
+    import torch
+    import paper_2602_24174_amd as T
+    from gpu_util import Rig
+    cfg = W.get_config("cfg1").scaled(dtype="bf16", n_layers=2, d_model=256, n_heads=4, n_kv_heads=2, head_dim=64, d_ffn=448,
+                                      vocab=1000, batch=28, prompt_len=40, gen_len=40, k=4, n_docs=1500, n_max=4)
+    rig = Rig(cfg, max_rows=16)
+    drafts = torch.zeros((cfg.batch, cfg.k), dtype=torch.int32, device="cuda")
+    acc = torch.zeros(cfg.batch, dtype=torch.int32, device="cuda")
+    emitted = torch.zeros((cfg.batch, cfg.k + 1), dtype=torch.int32, device="cuda")
+    runs = {}
+    try:
+        for graph, chains in ((0, 1), (1, 1), (0, 3), (1, 2), (1, 4)):
+            print(f"graph {graph} chains {chains}", flush=True)
+            T.tasc_config_set(T.TASC_CFG_STEP_GRAPH, graph)
+            T.tasc_config_set(T.TASC_CFG_CHAINS, chains)
+            T.tasc_session_prefill(rig.model, rig.session, rig.prompts, rig.prompt_off, cfg.gen_len)
+            steps = []
+            for s in range(7):
+                T.tasc_draft(rig.ng, rig.session, rig.params(), drafts)
+                T.tasc_verify_step(rig.model, rig.session, drafts, cfg.k, acc, emitted)
+                torch.cuda.synchronize()
+                steps.append((drafts.cpu().numpy().copy(), acc.cpu().numpy().copy(), emitted.cpu().numpy().copy(),
+                              [T.tasc_session_get_tokens(rig.session, b).copy() for b in (0, 13, 27)]))
+            out, st, _ = rig.generate()
+            g_out, _, _ = rig.generate(k=0)
+            assert (out == g_out).all(), f"graph {graph} chains {chains}: speculative output differs from greedy"
+            runs[(graph, chains)] = (steps, out, (st.steps, st.accepted, st.proposed, tuple(st.accept_hist)))
+    finally:
+        T.tasc_config_set(T.TASC_CFG_STEP_GRAPH, 1)
+        T.tasc_config_set(T.TASC_CFG_CHAINS, 0)
+    ref_steps, ref_out, ref_stats = runs[(0, 1)]
+    assert sum(int(a.sum()) for _, a, _, _ in ref_steps) > 0, "no draft was ever accepted: the test would compare nothing"
+    for key, (steps, out, stats) in runs.items():
+        for s, (a, b) in enumerate(zip(ref_steps, steps)):
+            assert (a[0] == b[0]).all() and (a[1] == b[1]).all(), f"{key} step {s}"
+            m = a[1]
+            for row in range(cfg.batch):
+                assert (a[2][row, :m[row] + 1] == b[2][row, :m[row] + 1]).all(), f"{key} step {s} sequence {row}"
+            assert all((x == y).all() for x, y in zip(a[3], b[3])), f"{key} step {s}"
+        assert (out == ref_out).all() and stats == ref_stats, key
+
+
 @pytest.mark.parametrize("shape", ["two_row_passes_long_keys", "one_chunk_many_sequences", "hd128_long_keys"])
 def test_staged_attention_shapes(shape):
     """The LDS-staged attention at the edges of its launch shapes: more than 64 (row, head) pairs per KV head (two row
