@@ -460,6 +460,15 @@ tasc_status tasc_calibration_read(const void* src, size_t bytes, int32_t passes,
 tasc_status tasc_calibration_handover(int32_t n_workgroups, int32_t stride, int32_t bytes, int32_t with_flags, void* stream,
                                       double* us_per_handover);
 
+/* Duration of one launch of the tiled bf16 GEMM out[M, N] = epilogue(A[M, K] W[N, K]^T) at a given shape, with the tile
+ * shape the forward would choose for it: the measuring stick for the projections of a verify step (Speculative Decoding:
+ * one forward over the k + 1 candidate rows of every sequence).  epilogue: 0 plain fp32 store, 1 residual add, 2 SwiGLU
+ * (bf16 out, N = 2 x d_ffn with gate and up rows interleaved), 4 fp32 partial sums of `slices` k-slices (1..8).  The operands
+ * are constant fills the call allocates and frees; *us_per_launch (HOST) = the mean of `iters` back-to-back launches after 3
+ * warm-up launches, from HIP events on `stream`.  Synchronises the stream.  Errors: TASC_EINVAL (shape), TASC_EHIP. */
+tasc_status tasc_calibration_gemm(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t slices, int32_t iters, void* stream,
+                                  double* us_per_launch);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
     "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_ngram_entropy_noalloc", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_tok_enrich", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
-    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_profile_durations", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read", "tasc_calibration_handover",
+    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_profile_durations", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read", "tasc_calibration_handover", "tasc_calibration_gemm",
 ]
 KERNEL_CLASSES = ["draft", "prepare", "norm", "gemm_qkv", "rope_kv", "attn", "gemm_o", "gemm_gu", "gemm_d", "lmhead", "accept",
                   "verify", "layers"]
@@ -116,6 +116,7 @@ def lib():
         L.tasc_calibration_mfma.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.tasc_calibration_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.tasc_calibration_handover.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+        L.tasc_calibration_gemm.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.tasc_profile_enable.argtypes = [C.c_uint32]
         L.tasc_profile_read.argtypes = [C.c_void_p, C.c_void_p]
         L.tasc_profile_durations.argtypes = [C.c_int32, C.c_void_p, C.c_int64, C.POINTER(C.c_int64)]
@@ -419,6 +420,13 @@ def tasc_calibration_read(src, passes=1, stream=None) -> float:
     """Read rate (GB/s) of a stream of independent 16-byte loads over the device tensor src (a multiple of 64 KB)."""
     out = C.c_double(0.0)
     _check(lib().tasc_calibration_read(_ptr(src), src.numel() * src.element_size(), passes, _stream(stream), C.byref(out)))
+    return out.value
+
+
+def tasc_calibration_gemm(M, N, K, epilogue=0, slices=1, iters=20, stream=None) -> float:
+    """Microseconds per launch of the tiled GEMM at this shape (epilogue 0 store, 1 residual, 2 SwiGLU, 4 partial sums)."""
+    out = C.c_double(0.0)
+    _check(lib().tasc_calibration_gemm(M, N, K, epilogue, slices, iters, _stream(stream), C.byref(out)))
     return out.value
 
 

@@ -211,6 +211,21 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
     }
 }
 
+tasc_status tiled_ready() {
+    if (g_tiled_ready) return TASC_OK;
+    tasc_status rc;
+    if ((rc = tiled_attrs<TEPI_STORE>()) != TASC_OK) return rc;
+    if ((rc = tiled_attrs<TEPI_RESID>()) != TASC_OK) return rc;
+    if ((rc = tiled_attrs<TEPI_SWIGLU>()) != TASC_OK) return rc;
+    if ((rc = tiled_attrs<TEPI_LMHEAD>()) != TASC_OK) return rc;
+    if ((rc = tiled_attrs<TEPI_PARTIAL>()) != TASC_OK) return rc;
+    TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<2>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(64) + 4 * TA_MAX_BLOCKS));
+    TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<4>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(128) + 4 * TA_MAX_BLOCKS));
+    g_tiled_ready = true;
+    return TASC_OK;
+}
+
+
 // how many ranges of sequences run the layers side by side when the caller leaves the choice to the library
 int tiled_auto_chains(const tasc_model_desc& c, int batch, int nq) {
     (void)c; (void)batch; (void)nq;
@@ -220,16 +235,9 @@ int tiled_auto_chains(const tasc_model_desc& c, int batch, int nq) {
 tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
-    if (!g_tiled_ready) {
-        tasc_status rc;
-        if ((rc = tiled_attrs<TEPI_STORE>()) != TASC_OK) return rc;
-        if ((rc = tiled_attrs<TEPI_RESID>()) != TASC_OK) return rc;
-        if ((rc = tiled_attrs<TEPI_SWIGLU>()) != TASC_OK) return rc;
-        if ((rc = tiled_attrs<TEPI_LMHEAD>()) != TASC_OK) return rc;
-        if ((rc = tiled_attrs<TEPI_PARTIAL>()) != TASC_OK) return rc;
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<2>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(64) + 4 * TA_MAX_BLOCKS));
-        TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<4>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(128) + 4 * TA_MAX_BLOCKS));
-        g_tiled_ready = true;
+    {
+        const tasc_status rc = tiled_ready();
+        if (rc != TASC_OK) return rc;
     }
     const int M_all = s->batch * nq;
     const int D = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim, F = c.d_ffn;
@@ -686,6 +694,50 @@ tasc_status tasc_pipe_arm(tasc_session* s, hipStream_t st) {
     k_fill_sentinel<<<dim3(1024), dim3(256), 0, st>>>((u64*)s->d.small_ws, units);
     TASC_LAUNCH_CHECK();
     s->ll_armed = true;
+    return TASC_OK;
+}
+
+extern "C" tasc_status tasc_calibration_gemm(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t slices, int32_t iters,
+                                             void* stream, double* us_per_launch) {
+    TASC_REQUIRE(us_per_launch && M >= 1 && M <= 65536 && N >= 128 && N <= (1 << 20) && N % 128 == 0 && K >= 64 && K <= 65536 && K % 64 == 0,
+                 "calibration_gemm: 1 <= M <= 65536, N a multiple of 128 up to 2^20, K a multiple of 64 up to 65536");
+    TASC_REQUIRE(epilogue == TEPI_STORE || epilogue == TEPI_RESID || epilogue == TEPI_SWIGLU || epilogue == TEPI_PARTIAL,
+                 "calibration_gemm: epilogue %d is none of store (0), residual add (1), SwiGLU (2), k-slice partial sums (4)", epilogue);
+    TASC_REQUIRE(slices >= 1 && slices <= TG_MAX_SLICES && (slices == 1 || epilogue == TEPI_PARTIAL) && K / 64 >= slices,
+                 "calibration_gemm: 1 .. %d k-slices, more than one only with the partial-sum epilogue", TG_MAX_SLICES);
+    TASC_REQUIRE(iters >= 1 && iters <= 10000, "calibration_gemm: 1 .. 10000 launches");
+    hipStream_t st = (hipStream_t)stream;
+    tasc_status rc = tiled_ready();
+    if (rc != TASC_OK) return rc;
+    const size_t a_bytes = (size_t)M * K * 2, w_bytes = (size_t)N * K * 2, o_bytes = (size_t)M * N * 4 * slices;
+    struct Tmp { void* p[3] = {nullptr, nullptr, nullptr}; ~Tmp() { for (void* q : p) if (q) (void)hipFree(q); } } t;
+    TASC_HIP(hipMalloc(&t.p[0], a_bytes));
+    TASC_HIP(hipMalloc(&t.p[1], w_bytes));
+    TASC_HIP(hipMalloc(&t.p[2], o_bytes));
+    TASC_HIP(hipMemsetAsync(t.p[0], 0x3c, a_bytes, st));       // bf16 0x3c3c = 0.0115: finite sums and SwiGLU arguments
+    TASC_HIP(hipMemsetAsync(t.p[1], 0x3c, w_bytes, st));
+    TASC_HIP(hipMemsetAsync(t.p[2], 0, o_bytes, st));
+    LmEpi none{};
+    auto launch = [&]() {
+        const BF16* A = (const BF16*)t.p[0];
+        if (epilogue == TEPI_STORE) launch_gemm<TEPI_STORE>(A, t.p[1], M, N, K, (float*)t.p[2], nullptr, none, 1, st);
+        else if (epilogue == TEPI_RESID) launch_gemm<TEPI_RESID>(A, t.p[1], M, N, K, (float*)t.p[2], nullptr, none, 1, st);
+        else if (epilogue == TEPI_SWIGLU) launch_gemm<TEPI_SWIGLU>(A, t.p[1], M, N, K, nullptr, (BF16*)t.p[2], none, 1, st);
+        else launch_gemm<TEPI_PARTIAL>(A, t.p[1], M, N, K, (float*)t.p[2], nullptr, none, slices, st);
+    };
+    struct Ev { hipEvent_t e[2] = {nullptr, nullptr}; ~Ev() { for (hipEvent_t q : e) if (q) (void)hipEventDestroy(q); } } ev;
+    TASC_HIP(hipEventCreate(&ev.e[0]));
+    TASC_HIP(hipEventCreate(&ev.e[1]));
+    for (int i = 0; i < 3; ++i) launch();
+    TASC_LAUNCH_CHECK();
+    TASC_HIP(hipEventRecord(ev.e[0], st));
+    for (int i = 0; i < iters; ++i) launch();
+    TASC_HIP(hipEventRecord(ev.e[1], st));
+    TASC_LAUNCH_CHECK();
+    TASC_HIP(hipEventSynchronize(ev.e[1]));
+    float ms = 0.f;
+    TASC_HIP(hipEventElapsedTime(&ms, ev.e[0], ev.e[1]));
+    *us_per_launch = (double)ms * 1e3 / iters;
     return TASC_OK;
 }
 
