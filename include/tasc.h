@@ -243,6 +243,8 @@ typedef struct {
  * source's most frequent successor; with none, the corpus' most frequent token.  A source whose
  * weight is 0 is not consulted.  Each proposal is appended to the running context of the next.
  *   drafts  DEVICE int32[batch, k]
+ * Limit: the kernel keeps a sequence's committed tokens in LDS, so the session's max_len (which includes the
+ * 2 * max_rows slack tasc_session_create asks for) must not exceed 4096 tokens; TASC_EINVAL otherwise.
  */
 tasc_status tasc_draft(const tasc_ngram* ng, tasc_session* s, const tasc_spec_params* p,
                        int32_t* drafts, void* stream);
@@ -285,6 +287,17 @@ tasc_status tasc_generate(const tasc_model* m, const tasc_ngram* ng, tasc_sessio
                           const int32_t* prompts, const int64_t* prompt_offsets, tasc_mem where,
                           int32_t max_new, const tasc_spec_params* p, int32_t* out_tokens,
                           int32_t* trace, int32_t trace_steps, tasc_gen_stats* stats, void* stream);
+
+/* Health of a session whose decode steps run on the persistent small-batch kernels (forwards of at most 16 rows on a
+ * bf16 model: one launch per step whose workgroups wait for each other's results).  Those kernels need all their
+ * workgroups resident at once, one per compute unit: the session must have the device to itself while a step runs (a
+ * kernel of another stream, session or process that occupies compute units can keep a workgroup from starting).  Every
+ * wait is bounded; a wait that runs out sets a flag in the session and the step's outputs (tokens, accept_len, emitted,
+ * the cache) are then undefined.  tasc_verify_step and tasc_draft do not read the flag (that would cost a host round trip
+ * per step); tasc_generate checks it at its end, and this call reads it on demand:
+ *   *timed_out (HOST) = 1 if a step of this session ran into a time-out since the last tasc_session_prefill (which
+ *   clears the flag and makes the session usable again), else 0.  Synchronises `stream`.  Errors: TASC_EINVAL, TASC_EHIP. */
+tasc_status tasc_session_status(tasc_session* s, int32_t* timed_out, void* stream);
 
 /* Copies sequence b's committed tokens (prompt + generated) to HOST int32[cap]; *n = how many.
  * Synchronises `stream`. */

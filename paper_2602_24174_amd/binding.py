@@ -21,7 +21,7 @@ EXPORTS = [
     "tasc_last_error", "tasc_ngram_build", "tasc_ngram_destroy", "tasc_ngram_export", "tasc_ngram_export_contexts",
     "tasc_ngram_unigram", "tasc_ngram_get_stats", "tasc_ngram_entropy", "tasc_ngram_entropy_noalloc", "tasc_model_bigram", "tasc_ngram_from_bigram", "tasc_tok_enrich", "tasc_model_create", "tasc_model_destroy", "tasc_session_kv_bytes",
     "tasc_session_workspace_bytes", "tasc_session_create", "tasc_session_destroy", "tasc_session_prefill", "tasc_draft",
-    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_profile_enable", "tasc_profile_read", "tasc_profile_durations", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read", "tasc_calibration_handover", "tasc_calibration_gemm",
+    "tasc_verify_step", "tasc_generate", "tasc_session_get_tokens", "tasc_session_status", "tasc_profile_enable", "tasc_profile_read", "tasc_profile_durations", "tasc_config_set", "tasc_profile_phases", "tasc_calibration_copy", "tasc_calibration_mfma", "tasc_calibration_read", "tasc_calibration_handover", "tasc_calibration_gemm",
 ]
 KERNEL_CLASSES = ["draft", "prepare", "norm", "gemm_qkv", "rope_kv", "attn", "gemm_o", "gemm_gu", "gemm_d", "lmhead", "accept",
                   "verify", "layers"]
@@ -110,6 +110,7 @@ def lib():
         L.tasc_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.POINTER(SpecParams), C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(GenStats), C.c_void_p]
         L.tasc_session_get_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
+        L.tasc_session_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]
         L.tasc_config_set.argtypes = [C.c_int32, C.c_int32]
         L.tasc_profile_phases.argtypes = [C.c_void_p, C.c_int64]
         L.tasc_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -356,6 +357,13 @@ def tasc_generate(model: Model, ng, s: Session, prompts, prompt_offsets, max_new
                                _where(prompts), max_new, C.byref(params), _ptr(out_tokens), _ptr(trace), trace_steps, C.byref(st),
                                _stream(stream)))
     return st
+
+
+def tasc_session_status(s: Session, stream=None) -> bool:
+    """True if a persistent-kernel step of this session ran into a wait time-out since its last prefill."""
+    flag = C.c_int32(0)
+    _check(lib().tasc_session_status(s.handle, C.byref(flag), _stream(stream)))
+    return bool(flag.value)
 
 
 def tasc_session_get_tokens(s: Session, b: int, stream=None) -> np.ndarray:

@@ -684,6 +684,15 @@ extern "C" tasc_status tasc_generate(const tasc_model* m, const tasc_ngram* ng, 
     return TASC_OK;
 }
 
+extern "C" tasc_status tasc_session_status(tasc_session* s, int32_t* timed_out, void* stream) {
+    TASC_REQUIRE(s && timed_out, "session_status: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    TASC_HIP(hipMemcpyAsync(s->host_counters, s->d.counters, 32 * 8, hipMemcpyDeviceToHost, st));
+    TASC_HIP(hipStreamSynchronize(st));
+    *timed_out = s->host_counters[TASC_CTR_BAR_ERR] != 0 ? 1 : 0;
+    return TASC_OK;
+}
+
 extern "C" tasc_status tasc_session_get_tokens(const tasc_session* s, int32_t b, int32_t* tokens, int32_t cap, int32_t* n,
                                                void* stream) {
     TASC_REQUIRE(s && n, "get_tokens: null argument");

@@ -90,7 +90,14 @@ __global__ __launch_bounds__(64) void k_draft(DraftArgs a) {
     const int N = a.n_tok[b];
     const int Nctx = a.ctx_gen ? N : min(N, a.n_prompt[b]);   // tokens the context statistics cover
     const int32_t* seq = a.tokens + (size_t)b * a.max_len;
-    for (int i = lane; i < N; i += 64) s_tok[i] = seq[i];
+    for (int i0 = 0; i0 < N; i0 += 256) {                  // four loads in flight per lane
+        int32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = seq[min(i0 + 64 * u + lane, N - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + 64 * u + lane < N) s_tok[i0 + 64 * u + lane] = v[u];
+    }
     for (int i = lane; i < kHashSlots; i += 64) s_tab[i] = 0;     // generation 0 = never used
     const u64 q = (u64)a.q16, qb = (u64)(65536 - a.q16);
     const int n_max = a.ng.n_max, bits = a.ng.bits;
@@ -140,18 +147,28 @@ __global__ __launch_bounds__(64) void k_draft(DraftArgs a) {
             } else {
                 // the positions that follow an occurrence of the token just appended: one compare pass, compacted
                 uint8_t* s_val = reinterpret_cast<uint8_t*>(s_dl);        // their new match lengths, parked until all old ones are read
-                for (int p0 = 1; p0 < Nctx; p0 += 64) {
-                    const int p = p0 + lane;
-                    const bool hit1 = p < Nctx && s_tok[p - 1] == x_prev;
-                    const u64 hit = __ballot(hit1);
-                    if (hit1) {
-                        const int ml = min((int)s_ml[p - 1] + 1, nsuf);
-                        const int at = n_new + __popcll(hit & lt_mask);
-                        s_pos[nxt][at] = (uint16_t)p;
-                        s_val[at] = (uint8_t)ml;
-                        lmax = max(lmax, ml);
+                for (int p0 = 1; p0 < Nctx; p0 += 256) {          // 256 positions per round: all their LDS reads in flight together
+                    bool hit1[4];
+                    int mlp[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int p = min(p0 + 64 * u + lane, Nctx - 1);
+                        hit1[u] = p0 + 64 * u + lane < Nctx && s_tok[p - 1] == x_prev;
+                        mlp[u] = (int)s_ml[p - 1];
                     }
-                    n_new += __popcll(hit);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int p = p0 + 64 * u + lane;
+                        const u64 hit = __ballot(hit1[u]);
+                        if (hit1[u]) {
+                            const int ml = min(mlp[u] + 1, nsuf);
+                            const int at = n_new + __popcll(hit & lt_mask);
+                            s_pos[nxt][at] = (uint16_t)p;
+                            s_val[at] = (uint8_t)ml;
+                            lmax = max(lmax, ml);
+                        }
+                        n_new += __popcll(hit);
+                    }
                 }
                 __builtin_amdgcn_s_waitcnt(0);
                 __builtin_amdgcn_wave_barrier();

@@ -14,6 +14,19 @@
 
 TascConfig g_tasc_config = {/*small_path*/ 2, /*small_grid*/ 0, /*layer_wgs*/ 0, /*layer_stride*/ 0, /*tiled_path*/ 1, /*xcd_local*/ 1,
                              /*layer_workers*/ 0, /*small_kernel*/ 1, /*pipe_share*/ 1, /*chains*/ 0, /*step_graph*/ 1};
+// One-time set-up (kernel attributes, the compute-unit count) is kept per device and done under a lock, so that calls
+// from several host threads, or sessions on different devices of one process, each find their own device prepared.
+#include <mutex>
+namespace {
+struct DevState { bool tiled_ready = false, small_ready = false, pipe_ready = false; int cu_count = 0; };
+DevState g_dev[16];
+std::mutex g_dev_mu;
+DevState& dev_state() {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    return g_dev[dev & 15];
+}
+}  // namespace
 static u64* g_phase_ts = nullptr;
 static int64_t g_phase_ts_cap = 0;
 
@@ -153,7 +166,6 @@ bool tiled_path_fits(const tasc_model_desc& c) {
            (c.head_dim == 32 || c.head_dim == 64 || c.head_dim == 128);
 }
 
-bool g_tiled_ready = false;
 
 // tile shapes: 128 x 128 on 4 waves, and 256 x 256 on 8 waves for row counts where the GEMMs are MFMA-bound.
 // Both reduce every output element over k in the same order, so the choice may depend on the row count.
@@ -212,7 +224,9 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
 }
 
 tasc_status tiled_ready() {
-    if (g_tiled_ready) return TASC_OK;
+    std::lock_guard<std::mutex> lock(g_dev_mu);
+    DevState& ds = dev_state();
+    if (ds.tiled_ready) return TASC_OK;
     tasc_status rc;
     if ((rc = tiled_attrs<TEPI_STORE>()) != TASC_OK) return rc;
     if ((rc = tiled_attrs<TEPI_RESID>()) != TASC_OK) return rc;
@@ -221,7 +235,7 @@ tasc_status tiled_ready() {
     if ((rc = tiled_attrs<TEPI_PARTIAL>()) != TASC_OK) return rc;
     TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<2>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(64) + 4 * TA_MAX_BLOCKS));
     TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<4>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(128) + 4 * TA_MAX_BLOCKS));
-    g_tiled_ready = true;
+    ds.tiled_ready = true;
     return TASC_OK;
 }
 
@@ -442,14 +456,13 @@ bool small_path_fits(const tasc_model* m, int batch, int nq, int max_blocks) {
            (nq * (c.n_heads / c.n_kv_heads)) >= 1;
 }
 
-int g_cu_count = 0;
-bool g_small_ready = false;
 
 tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, TascVerifyTail* tail,
                           hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
-    if (!g_small_ready) {
+    DevState& ds = dev_state();
+    if (std::lock_guard<std::mutex> lock(g_dev_mu); !ds.small_ready) {
         int dev = 0, cus = 0;
         TASC_HIP(hipGetDevice(&dev));
         TASC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
@@ -465,8 +478,8 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
             tasc_set_error("forward: the persistent kernel does not fit the device (%d compute units, %d blocks each)", cus, per_cu);
             return TASC_EHIP;
         }
-        g_cu_count = cus;
-        g_small_ready = true;
+        ds.cu_count = cus;
+        ds.small_ready = true;
     }
     SmallArgs a;
     a.layers = m->d_layers;
@@ -506,8 +519,8 @@ tasc_status forward_small(const tasc_model* m, tasc_session* s, int nq, int n_se
     a.phase_ts = g_phase_ts;
     a.phase_ts_wgs = g_phase_ts ? (int32_t)(g_phase_ts_cap / (2 * (int64_t)n_phases)) : 0;
     const int last = n_sel > 0 ? n_phases : n_lg_phases;   // without LM-head rows the step ends after the last layer
-    int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
-    grid = grid < g_cu_count ? grid : g_cu_count;            // every workgroup must be resident: at most one per compute unit
+    int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : ds.cu_count;
+    grid = grid < ds.cu_count ? grid : ds.cu_count;            // every workgroup must be resident: at most one per compute unit
     // Layer group.  The dispatcher deals workgroup ids round-robin over the 8 XCDs, so by default the group is
     // every 8th workgroup, 32 of them: one XCD's worth, which lets the 150 latency-bound layer phases hand
     // their activations over through that XCD's L2 (the kernel checks where it really runs and falls back
@@ -598,18 +611,17 @@ tasc_status pipe_attr() {
                                  PIPE_LDS_BYTES));
     return TASC_OK;
 }
-bool g_pipe_ready = false;
 
 tasc_status forward_pipe(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, TascVerifyTail* tail, int grid,
                          hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
-    if (!g_pipe_ready) {
+    if (std::lock_guard<std::mutex> lock(g_dev_mu); !dev_state().pipe_ready) {
         tasc_status rc;
         if ((rc = pipe_attr<1, 3>()) != TASC_OK || (rc = pipe_attr<2, 3>()) != TASC_OK || (rc = pipe_attr<4, 3>()) != TASC_OK ||
             (rc = pipe_attr<1, 6>()) != TASC_OK || (rc = pipe_attr<2, 6>()) != TASC_OK || (rc = pipe_attr<4, 6>()) != TASC_OK)
             return rc;
-        g_pipe_ready = true;
+        dev_state().pipe_ready = true;
     }
     if (!s->ll_armed) {
         tasc_status rc = tasc_pipe_arm(s, st);
@@ -764,13 +776,19 @@ tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, 
     const int decode_rows = s->max_rows < SMALL_ROWS ? s->max_rows : SMALL_ROWS;
     if (g_tasc_config.small_path != 0 && nq <= SMALL_ROWS && small_path_fits(m, s->batch, decode_rows, s->max_blocks)) {
         if (g_tasc_config.small_kernel != 0) {
-            if (g_cu_count == 0) {
-                int dev = 0;
-                TASC_HIP(hipGetDevice(&dev));
-                TASC_HIP(hipDeviceGetAttribute(&g_cu_count, hipDeviceAttributeMultiprocessorCount, dev));
+            int cus = 0;
+            {
+                std::lock_guard<std::mutex> lock(g_dev_mu);
+                DevState& ds = dev_state();
+                if (ds.cu_count == 0) {
+                    int dev = 0;
+                    TASC_HIP(hipGetDevice(&dev));
+                    TASC_HIP(hipDeviceGetAttribute(&ds.cu_count, hipDeviceAttributeMultiprocessorCount, dev));
+                }
+                cus = ds.cu_count;
             }
-            int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : g_cu_count;
-            grid = grid < g_cu_count ? grid : g_cu_count;      // every workgroup must be resident: at most one per compute unit
+            int grid = g_tasc_config.small_grid > 0 ? g_tasc_config.small_grid : cus;
+            grid = grid < cus ? grid : cus;      // every workgroup must be resident: at most one per compute unit
             if (pipe_path_fits(m, s->batch, decode_rows, s->max_blocks, grid)) return forward_pipe(m, s, nq, n_sel, logits_dbg, tail, grid, st);
         }
         return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);

@@ -210,6 +210,7 @@ def test_small_batch_fused_kernel(heads):
             out, st, tr = rig.generate(trace_steps=cfg.gen_len)
             g_out, g_st, _ = rig.generate(k=0)
             assert (out == g_out).all(), f"mode {mode}: speculative output differs from greedy"
+            assert not T.tasc_session_status(rig.session), f"mode {mode}: a wait of the persistent kernel timed out"
             for b in range(cfg.batch):
                 _replay(cfg, ref_tables, prompts[b].tolist(), tr[:, b], cfg.k, cfg.lambda_q16, cfg.p_min_ctx, out[b])
             # logits of a few verify steps
