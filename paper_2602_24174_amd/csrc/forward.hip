@@ -192,7 +192,7 @@ tasc_status tiled_attrs() {
 // launches out = epilogue(A W^T) with the tile shape that suits M; `slices` > 1 only for TEPI_PARTIAL
 template <int EPI>
 void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf, BF16* outb, const LmEpi& lm, int slices,
-                 hipStream_t st) {
+                 hipStream_t st, const RopeEpi& rp = RopeEpi{}) {
     // large tiles need enough of them to fill the chip: narrow outputs stay on the small tile (the k order, and so
     // every row's result, is the same for both shapes)
     const long large_wgs = (long)((M + 255) / 256) * ((N + 255) / 256) * slices;
@@ -204,22 +204,23 @@ void launch_gemm(const BF16* A, const void* Wm, int M, int N, int K, float* outf
         const int mt256 = (M + 255) / 256, mt192 = (M + 191) / 192;
         if (mt192 <= mt256 && mt192 * 192 < mt256 * 256) {
             dim3 g((unsigned)(mt192 * ((N + 255) / 256)), (unsigned)slices);
-            k_gemm_tiled<EPI, TILE_MID><<<g, dim3(512), TG_LDS_BYTES(256, 192), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+            k_gemm_tiled<EPI, TILE_MID><<<g, dim3(512), TG_LDS_BYTES(256, 192), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm, rp);
             return;
         }
         dim3 g((unsigned)(mt256 * ((N + 255) / 256)), (unsigned)slices);
-        k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+        k_gemm_tiled<EPI, TILE_LARGE><<<g, dim3(512), TG_LDS_BYTES(256, 256), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm, rp);
     } else {
         const long small_wgs = (long)((M + 127) / 128) * ((N + 127) / 128) * slices;
         if constexpr (EPI != TEPI_LMHEAD) {
-            if (small_wgs <= 128) {     // half of the compute units idle: halve the tile's width (a workgroup each, still)
+            // (the rotation epilogue needs whole heads inside a tile)
+            if (small_wgs <= 128 && !(EPI == TEPI_ROPE && rp.gm.hd > 64)) {     // half of the compute units idle: halve the tile's width (a workgroup each, still)
                 dim3 g((unsigned)(((M + 127) / 128) * ((N + 63) / 64)), (unsigned)slices);
-                k_gemm_tiled<EPI, TILE_NARROW><<<g, dim3(256), TG_LDS_BYTES(64, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+                k_gemm_tiled<EPI, TILE_NARROW><<<g, dim3(256), TG_LDS_BYTES(64, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm, rp);
                 return;
             }
         }
         dim3 g((unsigned)(((M + 127) / 128) * ((N + 127) / 128)), (unsigned)slices);
-        k_gemm_tiled<EPI, TILE_SMALL><<<g, dim3(256), TG_LDS_BYTES(128, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm);
+        k_gemm_tiled<EPI, TILE_SMALL><<<g, dim3(256), TG_LDS_BYTES(128, 128), st>>>(A, (const BF16*)Wm, M, N, K, outf, outb, lm, rp);
     }
 }
 
@@ -233,6 +234,7 @@ tasc_status tiled_ready() {
     if ((rc = tiled_attrs<TEPI_SWIGLU>()) != TASC_OK) return rc;
     if ((rc = tiled_attrs<TEPI_LMHEAD>()) != TASC_OK) return rc;
     if ((rc = tiled_attrs<TEPI_PARTIAL>()) != TASC_OK) return rc;
+    if ((rc = tiled_attrs<TEPI_ROPE>()) != TASC_OK) return rc;
     TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<2>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(64) + 4 * TA_MAX_BLOCKS));
     TASC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_staged<4>), hipFuncAttributeMaxDynamicSharedMemorySize, TA_LDS_BYTES(128) + 4 * TA_MAX_BLOCKS));
     ds.tiled_ready = true;
@@ -300,7 +302,6 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
         const size_t r0 = (size_t)b0 * nq;
         float* const x = d.x + r0 * D;
         BF16* const h = (BF16*)d.h + r0 * D;
-        float* const qkv = d.qkv + r0 * nqkv;
         BF16* const q = (BF16*)d.q + r0 * nqo;
         BF16* const att = (BF16*)d.att + r0 * nqo;
         BF16* const act = (BF16*)d.act + r0 * F;
@@ -347,14 +348,17 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
             }
             const int ks_qkv = slices(nqkv, D);
             {
+                // one slice: rotation and cache append ride in the projection's epilogue
                 PROF(TASC_KC_GEMM_QKV);
-                if (ks_qkv == 1) launch_gemm<TEPI_STORE>(h, w.wqkv, M, nqkv, D, qkv, nullptr, none, 1, st);
+                if (ks_qkv == 1)
+                    launch_gemm<TEPI_ROPE>(h, w.wqkv, M, nqkv, D, nullptr, q, none, 1, st,
+                                           RopeEpi{m->rope_cos, m->rope_sin, n_rows, pos0, block_tab, kv_layer, gm, c.max_pos});
                 else launch_gemm<TEPI_PARTIAL>(h, w.wqkv, M, nqkv, D, part, nullptr, none, ks_qkv, st);
             }
-            {
+            if (ks_qkv > 1) {
                 // the k-slices of a split projection are added inside the rotation kernel (same order as the reduction kernel)
                 PROF(TASC_KC_ROPE_KV);
-                k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(ks_qkv == 1 ? qkv : part, m->rope_cos, m->rope_sin, c.max_pos, n_rows,
+                k_rope_kv<BF16><<<dim3(M), dim3(256), 0, st>>>(part, m->rope_cos, m->rope_sin, c.max_pos, n_rows,
                                                              pos0, block_tab, gm, q, kv_layer, ks_qkv, (size_t)M * nqkv);
             }
             {

@@ -26,7 +26,20 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // below); the slice's sums go to outf[slice][M][N] and k_splitk_reduce adds the slices in order (plain store or
 // residual add).  Used where N is too narrow for the tile count to fill the chip; the number of slices depends on
 // N and K only.
-enum { TEPI_STORE = 0, TEPI_RESID = 1, TEPI_SWIGLU = 2, TEPI_LMHEAD = 3, TEPI_PARTIAL = 4 };
+// TEPI_ROPE: the fused q/k/v projection of a layer whose output is not sliced: the epilogue rotates the q and k heads (RoPE
+// at the row's position), writes q to outb and the new k / v rows straight into the row's cache page.
+enum { TEPI_STORE = 0, TEPI_RESID = 1, TEPI_SWIGLU = 2, TEPI_LMHEAD = 3, TEPI_PARTIAL = 4, TEPI_ROPE = 5 };
+
+struct RopeEpi {          // TEPI_ROPE only: what k_rope_kv takes
+    const float* cosT;        // [max_pos][hd / 2]
+    const float* sinT;
+    const int32_t* n_rows;    // [B] active rows of the sequence
+    const int32_t* pos0;      // [B] position of the sequence's first row
+    const int32_t* block_tab; // [B][max_blocks]
+    BF16* kv_layer;           // the layer's pages
+    KvGeom gm;
+    int32_t max_pos;
+};
 
 struct LmEpi {            // TEPI_LMHEAD only
     BiasCsr bias;
@@ -45,7 +58,7 @@ __device__ inline int tile_row(int i, int lane) { return 8 * (i >> 2) + 4 * (lan
 // (BN / WN) x (BM / WM) block as TI x TJ MFMA tiles of 32 x 32.
 template <int EPI, int BN, int BM, int WN, int WM>
 __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1, WN * WM >= 8 ? 2 : 1))) void k_gemm_tiled(const BF16* __restrict__ A, const BF16* __restrict__ W, int M, int N,
-                                                             int K, float* __restrict__ outf, BF16* __restrict__ outb, LmEpi lm) {
+                                                             int K, float* __restrict__ outf, BF16* __restrict__ outb, LmEpi lm, RopeEpi rp) {
     constexpr int THREADS = 64 * WN * WM;
     constexpr int SN = BN / WN, SM = BM / WM;          // the wave's span in n and m
     constexpr int TI = SN / 32, TJ = SM / 32;
@@ -130,6 +143,20 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
                 lm_end[j] = r0 + lm.bias_ptr[(size_t)m * (lm.n_strips + 1) + strip + 1];
             }
         }
+    }
+    // rotation epilogue: where every row of the tile goes (position, cache page and slot) is looked up now, under the main
+    // loop, instead of as a chain of dependent loads in the epilogue
+    __shared__ int32_t s_rpos[EPI == TEPI_ROPE ? BM : 1];      // table position of the row
+    __shared__ int32_t s_rslot[EPI == TEPI_ROPE ? BM : 1];     // slot inside its page, -1 for a row that appends nothing
+    __shared__ int32_t s_rpage[EPI == TEPI_ROPE ? BM : 1];     // its page
+    if (EPI == TEPI_ROPE && tid < BM) {
+        const int m = min(m0 + tid, M - 1);
+        const int b = m / rp.gm.nq, ir = m % rp.gm.nq;
+        const int pos = rp.pos0[b] + ir;
+        const bool active = ir < rp.n_rows[b];
+        s_rpos[tid] = pos < rp.max_pos ? pos : rp.max_pos - 1;
+        s_rslot[tid] = active ? pos % TASC_KV_BLOCK : -1;
+        s_rpage[tid] = active ? rp.block_tab[(size_t)b * rp.gm.max_blocks + pos / TASC_KV_BLOCK] : 0;
     }
     int kt_begin = 0, nk = K / TG_BK;
     if (EPI == TEPI_PARTIAL) {
@@ -342,20 +369,66 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(1,
         const int nwave = n0 + SN * wn;
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
-            if (j > 0) __builtin_amdgcn_wave_barrier();     // the reads of the block before are done (LDS serves a wave in order)
+            // the reads of the block before are done (LDS serves a wave in order; the rotation also reads other waves' blocks)
+            if (EPI == TEPI_ROPE) __syncthreads();
+            else if (j > 0) __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     *reinterpret_cast<float4*>(reg + (size_t)(lane & 31) * LDO + (32 * i + 8 * q + 4 * (lane >> 5)) * 4) =
                         make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            __builtin_amdgcn_wave_barrier();
+            if (EPI == TEPI_ROPE) __syncthreads();
+            else __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int p = 0; p < 32 / RPP; ++p) {
                 const int r = p * RPP + lane / CH, ch = lane % CH;
                 float4 vv = *reinterpret_cast<const float4*>(reg + (size_t)r * LDO + ch * 16);
                 const int m = m0 + SM * wm + 32 * j + r, n = nwave + ch * 4;
-                if (m < M && n < N) {
+                if (EPI == TEPI_ROPE) {
+                    // The lane whose 4 features lie in the first half of a head also takes their partners half a head on
+                    // (the same row, this wave's block or the block of a wave further along n: a tile holds whole heads)
+                    // and writes both.  Same arithmetic as k_rope_kv.
+                    const int hd = rp.gm.hd, half = hd / 2, e = n % hd, head = n / hd;
+                    if (m < M && n < N && e < half) {
+                        const int nl = SN * wn + ch * 4 + half;                      // partner's feature inside the tile
+                        const float4 cc = *reinterpret_cast<const float4*>(lds + (size_t)((nl / SN) * WM + wm) * 32 * LDO + (size_t)r * LDO + (nl % SN) * 4);
+                        const int rt = SM * wm + 32 * j + r;                          // row inside the tile
+                        const int tpos = s_rpos[rt], slot = s_rslot[rt];
+                        const bool active = slot >= 0;
+                        BF16* const page = rp.kv_layer + (size_t)s_rpage[rt] * rp.gm.page_elems;
+                        const float a4[4] = {vv.x, vv.y, vv.z, vv.w}, c4[4] = {cc.x, cc.y, cc.z, cc.w};
+                        if (head < rp.gm.H + rp.gm.Hkv) {
+                            const float4 cs = *reinterpret_cast<const float4*>(rp.cosT + (size_t)tpos * half + e);
+                            const float4 sn = *reinterpret_cast<const float4*>(rp.sinT + (size_t)tpos * half + e);
+                            const float c_[4] = {cs.x, cs.y, cs.z, cs.w}, s_[4] = {sn.x, sn.y, sn.z, sn.w};
+                            float ra[4], rc[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                ra[u] = a4[u] * c_[u] - c4[u] * s_[u];
+                                rc[u] = c4[u] * c_[u] + a4[u] * s_[u];
+                            }
+                            BF16* dst = nullptr;
+                            if (head < rp.gm.H) {
+                                dst = outb + (size_t)m * rp.gm.H * hd + head * hd + e;
+                            } else if (active) {
+                                dst = page + (size_t)((head - rp.gm.H) * TASC_KV_BLOCK + slot) * hd + e;
+                            }
+                            if (dst) {
+                                *reinterpret_cast<u32x2*>(dst) = pack_bf16x4(ra[0], ra[1], ra[2], ra[3]);
+                                *reinterpret_cast<u32x2*>(dst + half) = pack_bf16x4(rc[0], rc[1], rc[2], rc[3]);
+                            }
+                        } else if (active) {
+                            uint16_t* vt = reinterpret_cast<uint16_t*>(page) + (size_t)rp.gm.Hkv * TASC_KV_BLOCK * hd +
+                                           (size_t)((head - rp.gm.H - rp.gm.Hkv) * hd + e) * TASC_KV_BLOCK + slot;
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                vt[(size_t)u * TASC_KV_BLOCK] = f2bf(a4[u]);
+                                vt[(size_t)(half + u) * TASC_KV_BLOCK] = f2bf(c4[u]);
+                            }
+                        }
+                    }
+                } else if (m < M && n < N) {
                     float4* pp = reinterpret_cast<float4*>(outf + (size_t)m * N + n);
                     if (EPI == TEPI_RESID) {
                         const float4 old = *pp;
