@@ -25,6 +25,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+# HBM bytes of one verify step from rocprofv3 hardware counters (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter
+# reads for a plain copy kernel of known size); bench.py cannot collect counters itself, so the figure of the committed
+# counter runs is carried here, for the workload they were taken on only
+MEASURED_TRAFFIC = {"cfg5": 29473969869}
+MEASURED_TRAFFIC_SOURCE = "profiles/cfg5_verify_step_hbm_traffic.txt (bytes per verify step: every kernel of the step)"
 MFMA_PEAK_TFLOPS = 2500.0    # MI355X published dense bf16 matrix rate
 FP32_PEAK_TFLOPS = 157.3     # fp32 vector rate (the fp32 configuration runs on the type-generic kernels)
 
@@ -267,7 +272,7 @@ def main():
     mfma = {"bound": "mfma", "achieved": head.get("gemm_tflops"), "peak": head.get("matrix_peak_tflops"), "unit": "TFLOP/s",
             "frac": head.get("mfma_frac"), "algorithmic_flops": head["algorithmic_gemm_flops_per_verify_step"]}
     roofline = dict(mfma if (compute_bound and bf16) else hbm)
-    roofline.update({"traffic": None,
+    roofline.update({"traffic": MEASURED_TRAFFIC.get(cfg.name), "traffic_source": MEASURED_TRAFFIC_SOURCE if cfg.name in MEASURED_TRAFFIC else None,
                      "kernel": "verify step: every kernel of one target forward over batch x (k+1) rows, the LM head with argmax, and the accept "
                                "(HIP events around each step on the launch stream; median over the timed region)",
                      "median_launch_ms": med, "launches": int(head["verify_steps_per_generate"] * args.steps),
