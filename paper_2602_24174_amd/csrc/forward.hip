@@ -281,6 +281,9 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
             // (measured on the qkv / output / down projections of the 0.5B and 1.5B shapes)
             ks = nk / 12 > (24 + n_nt - 1) / n_nt ? nk / 12 : (24 + n_nt - 1) / n_nt;
         }
+        // beyond two 128-row tiles every slice's pass over rows x N partial sums costs more than the shorter k loop
+        // gains (the 1.5B shape's down projection in the step: 4 slices 4.40 ms per verify step, 8 slices 4.52 ms)
+        if (rows_ref > 256 && rows_ref < kLargeTileRows && ks > 4) ks = 4;
         ks = ks < nk / 4 ? ks : nk / 4;                       // slices of at least 4 k-steps
         ks = ks < TG_MAX_SLICES ? ks : TG_MAX_SLICES;
         return ks < 1 ? 1 : ks;
