@@ -25,6 +25,13 @@ def test_calibration_copy_read_and_mfma():
     assert 0.1 < local < 20.0 and 0.1 < chip < 50.0 and 0.1 < flags < 100.0
     with pytest.raises(T.TascError):
         T.tasc_calibration_handover(1, 1, 1024)            # needs two workgroups
+    t_store, t_swiglu, t_part = T.tasc_calibration_gemm(224, 1152, 896, 0), T.tasc_calibration_gemm(224, 9728, 896, 2), \
+        T.tasc_calibration_gemm(224, 896, 4864, 4, 6)
+    print(f"tiled GEMM at the 0.5B verify shapes: qkv {t_store:.1f} us, gate/up {t_swiglu:.1f} us, down in 6 slices {t_part:.1f} us", flush=True)
+    assert 1.0 < t_store < 200.0 and 1.0 < t_swiglu < 400.0 and 1.0 < t_part < 400.0
+    for bad in ((224, 1000, 896, 0, 1), (224, 1152, 900, 0, 1), (224, 1152, 896, 3, 1), (224, 1152, 896, 0, 2), (0, 1152, 896, 0, 1)):
+        with pytest.raises(T.TascError):
+            T.tasc_calibration_gemm(*bad)                  # N not a multiple of 128, K not of 64, LM-head epilogue, slices without partial sums, no rows
     with pytest.raises(T.TascError):
         T.tasc_calibration_read(buf[:1000], 1)             # not a multiple of 64 KB
     with pytest.raises(T.TascError):
