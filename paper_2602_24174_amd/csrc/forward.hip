@@ -248,7 +248,7 @@ int tiled_auto_chains(const tasc_model_desc& c, int batch, int nq) {
     return 1;
 }
 
-tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, hipStream_t st) {
+tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_sel, float* logits_dbg, bool decode, hipStream_t st) {
     const tasc_model_desc& c = m->desc;
     const TascSessDev& d = s->d;
     {
@@ -261,10 +261,13 @@ tasc_status forward_tiled(const tasc_model* m, tasc_session* s, int nq, int n_se
     KvGeom gm{H, Hkv, hd, nq, s->max_blocks, s->page_elems};
     LmEpi none{};
     // Narrow outputs (few column tiles) are computed in k-slices.  The slice count fixes the order in which a row's
-    // products are added, so it must be the same for every forward of a session (a greedy step, a verify step and a
-    // prompt chunk of one session differ in their row count): it depends on N, K and the session's batch only, never on
-    // the rows of the call.  rows_ref = 5 rows per sequence stands for the verify steps the session is sized for.
-    const int rows_ref = s->batch * 5;
+    // products are added, so it must be the same for every DECODE forward of a session (a greedy step and a verify step
+    // of one session differ in their row count, and speculative decoding must reproduce greedy decoding bit for bit): it
+    // depends on N, K and the session's batch only, never on the rows of the call; rows_ref = 5 rows per sequence
+    // stands for the verify steps the session is sized for.  A prompt forward is the same computation in the
+    // speculative and in the greedy run whatever its slice count, so it takes the count that suits its own rows (its
+    // chunks of batch x max_rows rows fill the chip without slices, and every slice is a pass over rows x N partial sums).
+    const int rows_ref = decode ? s->batch * 5 : s->batch * nq;
     auto slices = [&](int N, int K) {
         const int n_nt = (N + 127) / 128, nk = K / TG_BK;
         if (n_nt >= 32) return 1;
@@ -800,7 +803,7 @@ tasc_status tasc_forward_rows(const tasc_model* m, tasc_session* s, int32_t nq, 
         }
         return forward_small(m, s, nq, n_sel, logits_dbg, tail, st);
     }
-    if (g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc)) return forward_tiled(m, s, nq, n_sel, logits_dbg, st);
+    if (g_tasc_config.tiled_path != 0 && tiled_path_fits(m->desc)) return forward_tiled(m, s, nq, n_sel, logits_dbg, tail != nullptr, st);
     if (m->desc.dtype == TASC_F32) return forward_generic<float>(m, s, nq, n_sel, logits_dbg, st);
     return forward_generic<BF16>(m, s, nq, n_sel, logits_dbg, st);
 }
